@@ -1,0 +1,172 @@
+"""CPU oracle for the C-K-S conv-layer operators -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
+this package.  It never touches the GPU library and shares no code with it.
+
+The arithmetic lives in ``cks_oracle.c`` (plain C, double accumulation; the
+textbook operators of Section IV Eq. (1)-(3) with padding, zero insertion and
+dilation made explicit).  This module only builds that file with gcc, loads it
+with ctypes and marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cks_oracle.c")
+_LIB = os.path.join(_HERE, "libcks_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile cks_oracle.c -> libcks_oracle.so (gcc -O2 -fopenmp)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-std=c99", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        geo = [ctypes.c_int] * 9
+        for name in ("cko_conv_fwd", "cko_deconv", "cko_wgrad"):
+            f = getattr(lib, name)
+            f.argtypes = [fp, fp, dp] + geo + [ip, ctypes.c_int64]
+            f.restype = ctypes.c_int
+        lib.cko_brute.argtypes = [fp, fp, fp, dp, dp, dp] + geo
+        lib.cko_brute.restype = ctypes.c_int
+        lib.cko_filter_transpose.argtypes = [fp, fp] + [ctypes.c_int] * 4
+        lib.cko_filter_transpose.restype = ctypes.c_int
+        lib.cko_kernel_split.argtypes = [fp, fp] + [ctypes.c_int] * 5
+        lib.cko_kernel_split.restype = ctypes.c_int
+        lib.cko_mac_counts.argtypes = [ip] + geo
+        lib.cko_mac_counts.restype = ctypes.c_int
+        lib.cko_out_dim.argtypes = [ctypes.c_int] * 4
+        lib.cko_out_dim.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f32(a, shape):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.shape != tuple(shape):
+        raise ValueError("expected shape %s, got %s" % (tuple(shape), a.shape))
+    return a
+
+
+def _fptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _sample(sample):
+    if sample is None:
+        return None, None, 0
+    s = np.ascontiguousarray(sample, dtype=np.int64).ravel()
+    return s, s.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), s.size
+
+
+def out_dim(I, F, s, p):
+    """floor((I + 2p - F)/s) + 1."""
+    return _load().cko_out_dim(I, F, s, p)
+
+
+def _check(rc):
+    if rc != 0:
+        raise ValueError("oracle rejected the geometry (code %d)" % rc)
+
+
+def conv_fwd(X, W, stride, padding, sample=None):
+    """Eq. (1): Y[N,OH,OW,OC] (float64) from X[N,IH,IW,IC], W[OC,FH,FW,IC].
+
+    With ``sample`` (flat indices into Y) only those elements are returned."""
+    N, IH, IW, IC = X.shape
+    OC, FH, FW, _ = W.shape
+    X = _f32(X, (N, IH, IW, IC)); W = _f32(W, (OC, FH, FW, IC))
+    lib = _load()
+    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    s, sp, ns = _sample(sample)
+    out = np.empty(ns if s is not None else (N, OH, OW, OC), dtype=np.float64)
+    _check(lib.cko_conv_fwd(_fptr(X), _fptr(W), _dptr(out), N, IC, IH, IW, OC, FH, FW, stride, padding, sp, ns))
+    return out
+
+
+def deconv(dY, W, IH, IW, stride, padding, sample=None):
+    """Eq. (2): dX[N,IH,IW,IC] (float64) from dY[N,OH,OW,OC], W[OC,FH,FW,IC]."""
+    OC, FH, FW, IC = W.shape
+    N = dY.shape[0]
+    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    dY = _f32(dY, (N, OH, OW, OC)); W = _f32(W, (OC, FH, FW, IC))
+    lib = _load()
+    s, sp, ns = _sample(sample)
+    out = np.empty(ns if s is not None else (N, IH, IW, IC), dtype=np.float64)
+    _check(lib.cko_deconv(_fptr(dY), _fptr(W), _dptr(out), N, IC, IH, IW, OC, FH, FW, stride, padding, sp, ns))
+    return out
+
+
+def wgrad(X, dY, FH, FW, stride, padding, sample=None):
+    """Eq. (3): dW[OC,FH,FW,IC] (float64) from X[N,IH,IW,IC], dY[N,OH,OW,OC]."""
+    N, IH, IW, IC = X.shape
+    OC = dY.shape[3]
+    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    X = _f32(X, (N, IH, IW, IC)); dY = _f32(dY, (N, OH, OW, OC))
+    lib = _load()
+    s, sp, ns = _sample(sample)
+    out = np.empty(ns if s is not None else (OC, FH, FW, IC), dtype=np.float64)
+    _check(lib.cko_wgrad(_fptr(X), _fptr(dY), _dptr(out), N, IC, IH, IW, OC, FH, FW, stride, padding, sp, ns))
+    return out
+
+
+def brute(X, W, dY, stride, padding):
+    """7-deep scatter loop; returns (Y, dX, dW) as float64.  Tiny inputs only."""
+    N, IH, IW, IC = X.shape
+    OC, FH, FW, _ = W.shape
+    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    X = _f32(X, (N, IH, IW, IC)); W = _f32(W, (OC, FH, FW, IC)); dY = _f32(dY, (N, OH, OW, OC))
+    Y = np.empty((N, OH, OW, OC)); dX = np.empty((N, IH, IW, IC)); dW = np.empty((OC, FH, FW, IC))
+    _check(_load().cko_brute(_fptr(X), _fptr(W), _fptr(dY), _dptr(Y), _dptr(dX), _dptr(dW),
+                             N, IC, IH, IW, OC, FH, FW, stride, padding))
+    return Y, dX, dW
+
+
+def filter_transpose(W):
+    """Section IV.A: W[OC,FH,FW,IC] -> [FH,FW,IC,OC] (float32)."""
+    OC, FH, FW, IC = W.shape
+    W = _f32(W, (OC, FH, FW, IC))
+    out = np.empty((FH, FW, IC, OC), dtype=np.float32)
+    _check(_load().cko_filter_transpose(_fptr(W), _fptr(out), OC, FH, FW, IC))
+    return out
+
+
+def kernel_split(W, stride):
+    """Algorithm 2 Stage 1 in the paper's layout C[s,s,OC,ceil(FH/s),ceil(FW/s),IC] (float32)."""
+    OC, FH, FW, IC = W.shape
+    W = _f32(W, (OC, FH, FW, IC))
+    s = stride
+    out = np.empty((s, s, OC, -(-FH // s), -(-FW // s), IC), dtype=np.float32)
+    _check(_load().cko_kernel_split(_fptr(W), _fptr(out), OC, FH, FW, IC, s))
+    return out
+
+
+def mac_counts(N, IC, IH, IW, OC, FH, FW, stride, padding):
+    """dict(dense, useful, nominal_deconv, nominal_dilated) in multiply-adds, by enumeration."""
+    c = np.zeros(4, dtype=np.int64)
+    _check(_load().cko_mac_counts(c.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                  N, IC, IH, IW, OC, FH, FW, stride, padding))
+    return dict(dense=int(c[0]), useful=int(c[1]), nominal_deconv=int(c[2]), nominal_dilated=int(c[3]))

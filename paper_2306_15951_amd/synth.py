@@ -1,0 +1,67 @@
+"""Seeded synthetic inputs and the benchmark layer geometries.
+
+This module holds no arithmetic of the method: it only names layer shapes and
+draws random tensors.  Both the GPU tests/benchmark and the CPU oracle's tests
+take their inputs from here, so that both sides see identical bits.
+
+Layouts (paper, Section IV, paragraph before Eq. (1)):
+    X  [N, IH, IW, IC]     W [OC, FH, FW, IC]     dY [N, OH, OW, OC]     float32
+"""
+from __future__ import annotations
+
+from collections import namedtuple
+
+import numpy as np
+
+Layer = namedtuple("Layer", "name N IC IH IW OC FH FW stride padding")
+
+# Canonical conv-layer parameters of the benchmark configurations.  "cfg4a" is
+# the deconvolution-layer upsampler (16x16x256 -> 32x32x128, 4x4, s2, p1)
+# written from the convolution side: its forward pass is the deconvolution
+# operator, its input gradient the convolution operator.
+LAYERS = {
+    "cfg0": Layer("cfg0", 2, 4, 8, 8, 4, 3, 3, 1, 1),
+    "cfg1": Layer("cfg1", 128, 64, 32, 32, 64, 3, 3, 1, 1),
+    "cfg2": Layer("cfg2", 128, 128, 16, 16, 256, 3, 3, 2, 1),
+    "cfg3a": Layer("cfg3a", 256, 512, 7, 7, 512, 3, 3, 1, 1),
+    "cfg3b": Layer("cfg3b", 256, 512, 4, 4, 512, 3, 3, 1, 1),
+    "cfg4a": Layer("cfg4a", 64, 128, 32, 32, 256, 4, 4, 2, 1),
+    "cfg4b": Layer("cfg4b", 64, 3, 224, 224, 64, 7, 7, 2, 3),
+}
+
+BASE_SEED = 230615951
+
+
+def out_hw(L):
+    return ((L.IH + 2 * L.padding - L.FH) // L.stride + 1,
+            (L.IW + 2 * L.padding - L.FW) // L.stride + 1)
+
+
+def shapes(L):
+    OH, OW = out_hw(L)
+    return (L.N, L.IH, L.IW, L.IC), (L.OC, L.FH, L.FW, L.IC), (L.N, OH, OW, L.OC)
+
+
+def make_inputs(L, kind="normal", seed=0):
+    """Return (X, W, dY) as float32 numpy arrays.
+
+    kind = "normal":  X, dY ~ N(0,1); W ~ N(0, 2/(FH*FW*IC))  (He-normal)
+           "uniform": all three uniform in [-1, 1]
+           "int":     all three integers uniform in {-3..3}, stored as float32
+                      (every partial sum of every operator is then exact in
+                      float32 as long as 9 * K < 2^24)
+    """
+    xs, ws, ys = shapes(L)
+    rng = [np.random.default_rng([BASE_SEED, seed, i]) for i in range(3)]
+    if kind == "normal":
+        X = rng[0].standard_normal(xs, dtype=np.float32)
+        W = rng[1].standard_normal(ws, dtype=np.float32) * np.float32(np.sqrt(2.0 / (L.FH * L.FW * L.IC)))
+        dY = rng[2].standard_normal(ys, dtype=np.float32)
+    elif kind == "uniform":
+        X, W, dY = (r.uniform(-1.0, 1.0, size=s).astype(np.float32) for r, s in zip(rng, (xs, ws, ys)))
+    elif kind == "int":
+        X, W, dY = (r.integers(-3, 4, size=s).astype(np.float32) for r, s in zip(rng, (xs, ws, ys)))
+    else:
+        raise ValueError(kind)
+    return X, W.astype(np.float32), dY
+
