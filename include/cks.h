@@ -1,0 +1,132 @@
+/*
+ * cks.h -- C ABI of the C-K-S convolution-layer operators for AMD MI355X (gfx950).
+ *
+ * The three operators of a 2-D convolutional layer (paper: Section IV,
+ * Eq. (1)-(3)), computed without ever multiplying a padded or inserted zero:
+ *
+ *   cks_conv2d_fwd            Y  = conv2D(X, W)             ConvV2, Algorithm 1
+ *   cks_deconv2d              dX = deconv2D(dY, rot180(W))  KS-deconv-V2, Algorithm 2 / 2B
+ *   cks_dilated_conv2d_wgrad  dW = dilated_conv2D(X, dY)    Sk-dilated-V2, Algorithm 3B
+ *
+ * Tensors (Section IV, paragraph before Eq. (1); notation of Table I).  All are
+ * dense, row-major, float32, in DEVICE memory of the current HIP device:
+ *
+ *   X, dX   [N][H][W][C]          input feature maps / their gradient   (C = I_C)
+ *   Wt, dW  [OC][FH][FW][C]       filters / their gradient
+ *   Y, dY   [N][OH][OW][OC]       output feature maps / their gradient
+ *   OH = floor((H + 2*padding - FH) / stride) + 1, OW likewise (cks_out_dims).
+ *
+ * Common arguments: N batch, C input channels, H x W the size of X (always the
+ * larger, input side -- also for cks_deconv2d, whose output size cannot be
+ * recovered from OH when (H + 2*padding - FH) is not a multiple of stride),
+ * OC output channels, FH x FW filter size, stride and padding applied to both
+ * axes.
+ *
+ * Ownership: the caller owns every buffer, workspaces included; the library
+ * never allocates or frees device memory and keeps no device state.  Inputs are
+ * never written; outputs are completely overwritten (elements whose trimmed
+ * range is empty receive +0.0); inputs, outputs and workspace must not overlap.
+ * Pointers must be 4-byte aligned; 16-byte aligned pointers with C and OC
+ * multiples of 4 take the vector-load path.
+ *
+ * Execution: asynchronous on `stream` (a hipStream_t passed as void*, NULL is
+ * the default stream).  Calls on different streams are independent.
+ *
+ * Errors: every function returns a cks_status (0 = success, negative = error).
+ * On error nothing has been enqueued.  CKS_ERR_HIP means a HIP call failed;
+ * cks_last_hip_error() returns that hipError_t value (per calling thread).
+ */
+#ifndef CKS_H
+#define CKS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CKS_OK = 0,
+    CKS_ERR_NULL = -1,        /* a required pointer is NULL */
+    CKS_ERR_SHAPE = -2,       /* dimension <= 0, stride < 1, padding < 0, filter larger
+                                 than the padded input, or a tensor of 2^31 or more elements */
+    CKS_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than the *_workspace() size */
+    CKS_ERR_HIP = -4,         /* a HIP runtime call failed; see cks_last_hip_error() */
+    CKS_ERR_UNSUPPORTED = -5  /* valid but not implemented (stride > 64) */
+} cks_status;
+
+/* Output size of Eq. (1).  OH, OW may be NULL.  Returns CKS_ERR_SHAPE if the
+ * padded input is smaller than the filter. */
+int cks_out_dims(int H, int W, int FH, int FW, int stride, int padding, int *OH, int *OW);
+
+/* Multiply-adds that touch no padded / inserted zero: N*C*OC*S_h*S_w with
+ * S_h = sum over oh of (fh_e - fh_s) of Algorithm 1, S_w likewise.  All three
+ * operators of a layer perform exactly this many.  -1 on bad geometry. */
+int64_t cks_useful_macs(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+
+/* Bytes of workspace each operator needs for this geometry (0 = none; then
+ * ws may be NULL).  Returns 0 on bad geometry as well. */
+size_t cks_conv2d_fwd_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+size_t cks_deconv2d_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+size_t cks_dilated_conv2d_wgrad_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+
+/* ConvV2 (Section IV.A, Algorithm 1).  For every output position the filter is
+ * cut to [fh_s,fh_e) x [fw_s,fw_e), the taps that lie over real input:
+ *   Y[n,oh,ow,oc] = sum_{fh,fw in the trimmed range, c} X[n,oh*s-p+fh,ow*s-p+fw,c] * Wt[oc,fh,fw,c]
+ * X [N,H,W,C] in, Wt [OC,FH,FW,C] in, Y [N,OH,OW,OC] out. */
+int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
+                   int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/* KS-deconv-V2 (Section IV.B; Algorithm 2 Stage 1, Algorithm 2B Stage 2&3).
+ * Runs cks_kernel_split into the workspace, then cks_deconv2d_presplit.
+ * dY [N,OH,OW,OC] in, Wt [OC,FH,FW,C] in, dX [N,H,W,C] out. */
+int cks_deconv2d(const float *dY, const float *Wt, float *dX,
+                 int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                 void *ws, size_t ws_bytes, void *stream);
+
+/* Sk-dilated-V2 (Section IV.C, Algorithm 3B) with the split of the contraction
+ * axis G_K = N*OH*OW into segments and a final aggregation (Section IV.C,
+ * paragraph on map-reduce).  dY is read as it is, X with a leaping step equal
+ * to the stride; per filter tap only the (oh,ow) whose X element exists are
+ * visited.  The partial sums live in the workspace and are added in a fixed
+ * order, so results are reproducible bit for bit.
+ * X [N,H,W,C] in, dY [N,OH,OW,OC] in, dW [OC,FH,FW,C] out. */
+int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
+                             int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/* ---- the stages on their own (what the three calls above are made of) ---- */
+
+/* Stage 1 of KS-deconv (Section IV.B, Algorithm 2 Stage 1): rotate the filter
+ * by 180 degrees and split it into stride*stride sub-kernels.  Sub-kernel (y,x)
+ * holds the taps fh = y + (oph-ch)*stride, fw = x + (opw-cw)*stride with
+ * oph = ceil((FH-y)/stride) - 1, opw likewise.  The result is the paper's
+ * zero-padded 6-D tensor with the two channel axes exchanged, so that the
+ * contraction index (ch,cw,oc) of Stage 2 is contiguous:
+ *   Cs[stride][stride][C][ceil(FH/stride)][ceil(FW/stride)][OC]
+ * cks_kernel_split_bytes gives its size.  Every element of Cs is written. */
+size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride);
+int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream);
+
+/* Stage 2&3 of KS-deconv-V2 (Algorithm 2B) on an already split filter. */
+int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
+                          int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                          void *stream);
+
+/* Filter transposition of Section IV.A (last paragraph):
+ * Wt[OC][FH][FW][C] -> Wout[FH][FW][C][OC]. */
+int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, int FW, void *stream);
+
+/* Number of segments the contraction axis of cks_dilated_conv2d_wgrad is split
+ * into for this geometry (the paper's G_Z); 0 on bad geometry. */
+int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+
+const char *cks_strerror(int status);
+int cks_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKS_H */

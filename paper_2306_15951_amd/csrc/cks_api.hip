@@ -1,0 +1,338 @@
+// Host side of libcks: argument checking, tile selection and kernel launches
+// behind the C ABI declared in include/cks.h.  gfx950 only.
+#include "../../include/cks.h"
+
+#include <hip/hip_runtime.h>
+
+#include "cks_pack.h"
+#include "cks_pixel_gemm.h"
+#include "cks_rowrun_gemm.h"
+
+namespace {
+
+using namespace cks;
+
+constexpr int kCUs = 256;  // compute units of one MI355X
+
+thread_local int g_last_hip_error = 0;
+
+struct Geo {
+    int N, C, H, W, OC, FH, FW, s, p, OH, OW;
+};
+
+inline bool fits_i31(long long v) { return v > 0 && v < (1LL << 31); }
+
+int check_geo(Geo &g, int N, int C, int H, int W, int OC, int FH, int FW, int s, int p)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || s < 1 || p < 0) return CKS_ERR_SHAPE;
+    if ((long long)H + 2LL * p < FH || (long long)W + 2LL * p < FW) return CKS_ERR_SHAPE;
+    if (p > (1 << 20) || s > (1 << 20)) return CKS_ERR_SHAPE;
+    g = Geo{N, C, H, W, OC, FH, FW, s, p, (H + 2 * p - FH) / s + 1, (W + 2 * p - FW) / s + 1};
+    if (!fits_i31((long long)N * H * W * C) || !fits_i31((long long)OC * FH * FW * C) ||
+        !fits_i31((long long)N * g.OH * g.OW * OC))
+        return CKS_ERR_SHAPE;
+    return CKS_OK;
+}
+
+inline int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return CKS_ERR_HIP;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <typename K, typename P>
+int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st)
+{
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), lds, st, params);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CKS_OK : hip_fail(e);
+}
+
+// ---------------------------------------------------------------- ConvV2 / KS-deconv Stage 2&3
+
+template <int OP, int BM, int BN, int WM, int WN>
+int launch_rowrun(RowRunParams P, int positions, int rows, int cols, bool vec, hipStream_t st)
+{
+    P.mTiles = (rows + BM - 1) / BM;
+    P.nTiles = (cols + BN - 1) / BN;
+    const long long total = (long long)positions * P.mTiles * P.nTiles;
+    if (!fits_i31(total + kXcds)) return CKS_ERR_SHAPE;
+    P.total = (int)total;
+    P.perXcd = (P.total + kXcds - 1) / kXcds;
+    const int blocks = P.perXcd * kXcds;
+    const size_t lds = rowrun_lds_bytes<BM, BN>();
+    if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, true>, P, blocks, lds, st);
+    return launch(rowrun_gemm<OP, BM, BN, WM, WN, false>, P, blocks, lds, st);
+}
+
+template <int OP>
+int dispatch_rowrun(const RowRunParams &P, int positions, int rows, int cols, bool vec, hipStream_t st)
+{
+    // rows = batch, cols = output channels of this operator.  Prefer the
+    // largest tile that still yields at least two workgroups per compute unit.
+    int bm = rows >= 96 ? 128 : 64;
+    int bn = cols >= 96 ? 128 : (cols >= 48 ? 64 : 32);
+    if (bn == 32) bm = 128;
+    auto blocks = [&](int m, int n) { return (long long)positions * ((rows + m - 1) / m) * ((cols + n - 1) / n); };
+    if (bm == 128 && bn == 128 && blocks(bm, bn) < 2 * kCUs) bn = 64;
+    if (bm == 128 && bn == 64 && blocks(bm, bn) < 2 * kCUs) bm = 64;
+    if (bm == 128 && bn == 128) return launch_rowrun<OP, 128, 128, 2, 2>(P, positions, rows, cols, vec, st);
+    if (bm == 128 && bn == 64) return launch_rowrun<OP, 128, 64, 2, 2>(P, positions, rows, cols, vec, st);
+    if (bm == 64 && bn == 128) return launch_rowrun<OP, 64, 128, 2, 2>(P, positions, rows, cols, vec, st);
+    if (bm == 64 && bn == 64) return launch_rowrun<OP, 64, 64, 2, 2>(P, positions, rows, cols, vec, st);
+    return launch_rowrun<OP, 128, 32, 4, 1>(P, positions, rows, cols, vec, st);
+}
+
+RowRunParams rowrun_params(const Geo &g, const float *A, const float *B, float *Out)
+{
+    RowRunParams P{};
+    P.A = A; P.B = B; P.Out = Out;
+    P.N = g.N; P.IC = g.C; P.IH = g.H; P.IW = g.W; P.OC = g.OC; P.OH = g.OH; P.OW = g.OW;
+    P.FH = g.FH; P.FW = g.FW; P.s = g.s; P.p = g.p;
+    P.CHp = (g.FH + g.s - 1) / g.s;
+    P.CWp = (g.FW + g.s - 1) / g.s;
+    return P;
+}
+
+size_t split_bytes(int C, int OC, int FH, int FW, int s)
+{
+    return sizeof(float) * (size_t)s * s * C * ((FH + s - 1) / s) * ((FW + s - 1) / s) * OC;
+}
+
+template <int MODE>
+int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int s, hipStream_t st)
+{
+    PackParams P{};
+    P.W = Wt; P.Out = Out; P.IC = C; P.OC = OC; P.FH = FH; P.FW = FW; P.s = s;
+    P.CHp = (FH + s - 1) / s;
+    P.CWp = (FW + s - 1) / s;
+    P.ocTiles = (OC + 31) / 32;
+    P.icTiles = (C + 31) / 32;
+    const long long slots = MODE == PACK_SPLIT ? (long long)s * s * P.CHp * P.CWp : (long long)FH * FW;
+    const long long blocks = slots * P.ocTiles * P.icTiles;
+    if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
+    return launch(pack_filter<MODE>, P, (int)blocks, 0, st);
+}
+
+// ---------------------------------------------------------------- Sk-dilated
+
+struct WgradPlan {
+    int bm, bn, mTiles, nTiles, GZ;
+};
+
+// G_Z: enough segments that the grid has about four workgroups per compute
+// unit, but never segments shorter than 512 pixels (Section IV.C: the number
+// of segments trades parallelism against the memory for partial sums).
+WgradPlan plan_wgrad(const Geo &g)
+{
+    WgradPlan w;
+    w.bm = g.OC >= 96 ? 128 : 64;
+    w.bn = g.C >= 96 ? 128 : 64;
+    w.mTiles = (g.OC + w.bm - 1) / w.bm;
+    w.nTiles = (g.C + w.bn - 1) / w.bn;
+    long long tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
+    if (w.bm == 128 && w.bn == 128 && tiles < kCUs / 2) {
+        w.bn = 64;
+        w.nTiles = (g.C + 63) / 64;
+        tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
+    }
+    const long long K = (long long)g.N * g.OH * g.OW;
+    long long gz = (4LL * kCUs + tiles - 1) / tiles;
+    gz = gz < K / 512 ? gz : K / 512;
+    if (gz < 1) gz = 1;
+    if (gz > 256) gz = 256;
+    w.GZ = (int)gz;
+    return w;
+}
+
+template <int BM, int BN>
+int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
+{
+    const size_t lds = pixel_lds_bytes<BM, BN>();
+    const int blocks = P.perXcd * kXcds;
+    if (veca && vecb) return launch(pixel_gemm<BM, BN, 2, 2, true, true>, P, blocks, lds, st);
+    if (veca) return launch(pixel_gemm<BM, BN, 2, 2, true, false>, P, blocks, lds, st);
+    if (vecb) return launch(pixel_gemm<BM, BN, 2, 2, false, true>, P, blocks, lds, st);
+    return launch(pixel_gemm<BM, BN, 2, 2, false, false>, P, blocks, lds, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int cks_out_dims(int H, int W, int FH, int FW, int stride, int padding, int *OH, int *OW)
+{
+    Geo g;
+    int rc = check_geo(g, 1, 1, H, W, 1, FH, FW, stride, padding);
+    if (rc != CKS_OK) return rc;
+    if (OH) *OH = g.OH;
+    if (OW) *OW = g.OW;
+    return CKS_OK;
+}
+
+int64_t cks_useful_macs(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return -1;
+    auto S = [&](int I, int F, int O) {
+        int64_t t = 0;
+        for (int o = 0; o < O; ++o) {
+            int i0 = o * g.s - g.p;
+            int lo = -i0 > 0 ? -i0 : 0, hi = I - i0 < F ? I - i0 : F;
+            if (hi > lo) t += hi - lo;
+        }
+        return t;
+    };
+    return (int64_t)N * C * OC * S(H, FH, g.OH) * S(W, FW, g.OW);
+}
+
+size_t cks_conv2d_fwd_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    (void)N; (void)C; (void)H; (void)W; (void)OC; (void)FH; (void)FW; (void)stride; (void)padding;
+    return 0;  // the forward operator reads the filter in its given layout
+}
+
+size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride)
+{
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || stride < 1) return 0;
+    return split_bytes(C, OC, FH, FW, stride);
+}
+
+size_t cks_deconv2d_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
+    return split_bytes(C, OC, FH, FW, stride);
+}
+
+int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
+    return plan_wgrad(g).GZ;
+}
+
+size_t cks_dilated_conv2d_wgrad_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
+    const WgradPlan w = plan_wgrad(g);
+    return w.GZ > 1 ? sizeof(float) * (size_t)w.GZ * OC * FH * FW * C : 0;
+}
+
+int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
+                   int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (rc != CKS_OK) return rc;
+    if (!X || !Wt || !Y) return CKS_ERR_NULL;
+    const bool vec = (C % 4 == 0) && aligned16(X) && aligned16(Wt);
+    return dispatch_rowrun<OP_FWD>(rowrun_params(g, X, Wt, Y), g.OH * g.OW, N, OC, vec, (hipStream_t)stream);
+}
+
+int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream)
+{
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || stride < 1) return CKS_ERR_SHAPE;
+    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
+    if (!Wt || !Cs) return CKS_ERR_NULL;
+    return launch_pack<PACK_SPLIT>(Wt, Cs, C, OC, FH, FW, stride, (hipStream_t)stream);
+}
+
+int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, int FW, void *stream)
+{
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0) return CKS_ERR_SHAPE;
+    if (!fits_i31((long long)C * OC * FH * FW)) return CKS_ERR_SHAPE;
+    if (!Wt || !Wout) return CKS_ERR_NULL;
+    return launch_pack<PACK_TRANSPOSE>(Wt, Wout, C, OC, FH, FW, 1, (hipStream_t)stream);
+}
+
+int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
+                          int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                          void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (rc != CKS_OK) return rc;
+    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
+    if (!dY || !Cs || !dX) return CKS_ERR_NULL;
+    const bool vec = (OC % 4 == 0) && aligned16(dY) && aligned16(Cs);
+    return dispatch_rowrun<OP_DECONV>(rowrun_params(g, dY, Cs, dX), H * W, N, C, vec, (hipStream_t)stream);
+}
+
+int cks_deconv2d(const float *dY, const float *Wt, float *dX,
+                 int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (rc != CKS_OK) return rc;
+    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
+    if (!dY || !Wt || !dX) return CKS_ERR_NULL;
+    if (!ws || ws_bytes < split_bytes(C, OC, FH, FW, stride)) return CKS_ERR_WORKSPACE;
+    rc = cks_kernel_split(Wt, (float *)ws, C, OC, FH, FW, stride, stream);
+    if (rc != CKS_OK) return rc;
+    return cks_deconv2d_presplit(dY, (const float *)ws, dX, N, C, H, W, OC, FH, FW, stride, padding, stream);
+}
+
+int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
+                             int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (rc != CKS_OK) return rc;
+    if (!X || !dY || !dW) return CKS_ERR_NULL;
+    const WgradPlan w = plan_wgrad(g);
+    const long slice = (long)OC * FH * FW * C;
+    if (w.GZ > 1 && (!ws || ws_bytes < sizeof(float) * (size_t)w.GZ * slice)) return CKS_ERR_WORKSPACE;
+    const long long total = (long long)w.GZ * FH * FW * w.mTiles * w.nTiles;
+    if (!fits_i31(total + kXcds)) return CKS_ERR_SHAPE;
+
+    PixelGemmParams P{};
+    P.X = X; P.dY = dY; P.Out = w.GZ > 1 ? (float *)ws : dW;
+    P.N = N; P.IC = C; P.IH = H; P.IW = W; P.OC = OC; P.OH = g.OH; P.OW = g.OW;
+    P.FH = FH; P.FW = FW; P.s = stride; P.p = padding;
+    P.GZ = w.GZ; P.mTiles = w.mTiles; P.nTiles = w.nTiles;
+    P.total = (int)total;
+    P.perXcd = (P.total + kXcds - 1) / kXcds;
+    P.sliceElems = slice;
+    const bool veca = (OC % 4 == 0) && aligned16(dY);
+    const bool vecb = (C % 4 == 0) && aligned16(X);
+    hipStream_t st = (hipStream_t)stream;
+    if (w.bm == 128 && w.bn == 128) rc = launch_pixel<128, 128>(P, veca, vecb, st);
+    else if (w.bm == 128 && w.bn == 64) rc = launch_pixel<128, 64>(P, veca, vecb, st);
+    else if (w.bm == 64 && w.bn == 128) rc = launch_pixel<64, 128>(P, veca, vecb, st);
+    else rc = launch_pixel<64, 64>(P, veca, vecb, st);
+    if (rc != CKS_OK || w.GZ == 1) return rc;
+    hipLaunchKernelGGL(reduce_slices, dim3((unsigned)((slice + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                       (const float *)ws, dW, slice, w.GZ);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CKS_OK : hip_fail(e);
+}
+
+const char *cks_strerror(int status)
+{
+    switch (status) {
+        case CKS_OK: return "success";
+        case CKS_ERR_NULL: return "a required pointer is NULL";
+        case CKS_ERR_SHAPE: return "invalid or too large tensor geometry";
+        case CKS_ERR_WORKSPACE: return "workspace missing or too small";
+        case CKS_ERR_HIP: return "HIP runtime error (see cks_last_hip_error)";
+        case CKS_ERR_UNSUPPORTED: return "geometry not supported";
+        default: return "unknown status";
+    }
+}
+
+int cks_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

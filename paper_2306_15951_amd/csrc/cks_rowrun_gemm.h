@@ -1,0 +1,239 @@
+// ConvV2 (Algorithm 1) and KS-deconv-V2 Stage 2&3 (Algorithm 2B) as one
+// position-uniform fp32-MFMA GEMM.
+//
+// Both operators have the same shape once an output POSITION is fixed
+// ((oh,ow) of Y, resp. (ih,iw) of dX):
+//
+//     Out[n, pos, j] = sum over trimmed taps, channel  A[n, tap, ch] * B[j, tap, ch]
+//
+// with n the batch index (GEMM rows), j the output channel (GEMM columns), and
+// the trimmed tap range the SAME for every n and j.  Better still, in NHWC
+// the taps of one filter row are adjacent pixels, so for one fh (resp. ch) the
+// contraction index (fw, ic) is one contiguous run of (fw_e - fw_s)*IC floats
+// in the activation row AND in the filter row:
+//
+//   ConvV2:    A = X,  B = W[oc][fh][fw][ic]              run over (fw, ic)
+//   KS-deconv: A = dY, B = Cs[y][x][ic][ch][cw][oc]       run over (cw, oc)
+//
+// So a workgroup owns (position, 128/64 batch rows, 128/64/32 channels), knows its
+// trim as scalars, and walks  nruns x ceil(L/32)  K-chunks; trimming costs
+// nothing but two pointer offsets and a shorter loop (Section IV.A: "moving
+// pointers and restricting memory-access"), no lane ever multiplies a padded
+// or inserted zero, and no per-element bounds test exists in the loop.
+#pragma once
+#include "cks_device.h"
+
+namespace cks {
+
+enum { OP_FWD = 0, OP_DECONV = 1 };
+
+struct RowRunParams {
+    const float *A;   // X (fwd) or dY (deconv)
+    const float *B;   // W (fwd) or split kernels Cs (deconv)
+    float *Out;       // Y (fwd) or dX (deconv)
+    int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
+    int CHp, CWp;     // ceil(FH/s), ceil(FW/s): padded sub-kernel extents
+    int mTiles, nTiles, total, perXcd;
+};
+
+struct RunSet {
+    long a0, b0, o0;          // float offsets of the first run in A-row 0, B-row 0, Out-row 0
+    long aRun, bRun;          // float distance between consecutive runs
+    long strideA, strideB, strideO;
+    int nruns, L, NC;         // runs, floats per run, number of output channels
+};
+
+// The a-th index of [0, I) when indices are listed class by class, class
+// y = (i + p) mod s, y = 0, 1, ...  (sub-kernel extents shrink with y, so the
+// classes with most work come first).
+__device__ inline int class_major_index(int a, int I, int s, int p)
+{
+    for (int y = 0; y < s; ++y) {
+        int i0 = ((y - p) % s + s) % s;
+        int cnt = i0 < I ? (I - 1 - i0) / s + 1 : 0;
+        if (a < cnt) return i0 + a * s;
+        a -= cnt;
+    }
+    return 0;  // not reached for 0 <= a < I
+}
+
+template <int OP>
+__device__ inline RunSet decode_position(const RowRunParams &P, int pos)
+{
+    RunSet R;
+    if (OP == OP_FWD) {
+        // Algorithm 1: trim [fh_s,fh_e) x [fw_s,fw_e) of the filter at (oh,ow).
+        // Interior positions (full filter, most work) are issued first.
+        int a = pos / P.OW, b = pos - a * P.OW;
+        int oh = (a + cdiv_any(P.p, P.s)) % P.OH, ow = (b + cdiv_any(P.p, P.s)) % P.OW;
+        int ih_s = oh * P.s - P.p, iw_s = ow * P.s - P.p;
+        int fh_s = max(-ih_s, 0), fh_e = min(P.IH - ih_s, P.FH);
+        int fw_s = max(-iw_s, 0), fw_e = min(P.IW - iw_s, P.FW);
+        R.nruns = max(fh_e - fh_s, 0);
+        R.L = max(fw_e - fw_s, 0) * P.IC;
+        R.a0 = ((long)(ih_s + fh_s) * P.IW + (iw_s + fw_s)) * P.IC;
+        R.aRun = (long)P.IW * P.IC;
+        R.strideA = (long)P.IH * P.IW * P.IC;
+        R.b0 = ((long)fh_s * P.FW + fw_s) * P.IC;
+        R.bRun = (long)P.FW * P.IC;
+        R.strideB = (long)P.FH * P.FW * P.IC;
+        R.o0 = ((long)oh * P.OW + ow) * P.OC;
+        R.strideO = (long)P.OH * P.OW * P.OC;
+        R.NC = P.OC;
+    } else {
+        // Algorithm 2B: class (y,x) of (ih,iw), its sub-kernel extent CH x CW,
+        // the window start (oh_s,ow_s) in dY and the trim [ch_s,ch_e) x [cw_s,cw_e).
+        int a = pos / P.IW, b = pos - a * P.IW;
+        int ih = class_major_index(a, P.IH, P.s, P.p), iw = class_major_index(b, P.IW, P.s, P.p);
+        int y = (ih + P.p) % P.s, x = (iw + P.p) % P.s;
+        int CH = y < P.FH ? (P.FH - y + P.s - 1) / P.s : 0;
+        int CW = x < P.FW ? (P.FW - x + P.s - 1) / P.s : 0;
+        int oh_s = (ih + P.p - y) / P.s - (CH - 1), ow_s = (iw + P.p - x) / P.s - (CW - 1);
+        int ch_s = max(-oh_s, 0), ch_e = min(P.OH - oh_s, CH);
+        int cw_s = max(-ow_s, 0), cw_e = min(P.OW - ow_s, CW);
+        R.nruns = max(ch_e - ch_s, 0);
+        R.L = max(cw_e - cw_s, 0) * P.OC;
+        R.a0 = ((long)(oh_s + ch_s) * P.OW + (ow_s + cw_s)) * P.OC;
+        R.aRun = (long)P.OW * P.OC;
+        R.strideA = (long)P.OH * P.OW * P.OC;
+        R.strideB = (long)P.CHp * P.CWp * P.OC;
+        R.b0 = (long)(y * P.s + x) * P.IC * R.strideB + ((long)ch_s * P.CWp + cw_s) * P.OC;
+        R.bRun = (long)P.CWp * P.OC;
+        R.o0 = ((long)ih * P.IW + iw) * P.IC;   // Stage 3: the class result lands at its own (ih,iw)
+        R.strideO = (long)P.IH * P.IW * P.IC;
+        R.NC = P.IC;
+    }
+    if (R.nruns == 0 || R.L == 0) { R.nruns = 0; R.L = 0; R.a0 = 0; R.b0 = 0; }
+    return R;
+}
+
+// Workgroup tile BM (batch rows) x BN (channels), K-chunk of 32 floats, LDS
+// double-buffered, rows padded to 36 floats so that the 16-byte fragment reads
+// of 32 consecutive rows spread over all banks.  4 waves as WAVES_M x WAVES_N,
+// each owning (BM/WAVES_M) x (BN/WAVES_N) as 32x32 MFMA blocks.
+template <int BM, int BN>
+constexpr size_t rowrun_lds_bytes() { return (size_t)2 * (BM + BN) * 36 * sizeof(float); }
+
+template <int OP, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC>
+__global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
+{
+    constexpr int KC = 32, LDK = KC + 4;
+    constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
+    constexpr int PA = BM / 32, PB = BN / 32;
+    static_assert(WAVES_M * WAVES_N == 4 && TM >= 1 && TN >= 1, "4 waves per workgroup");
+
+    extern __shared__ __align__(16) float smem[];
+    float *As = smem;                 // [2][BM][LDK]
+    float *Bs = smem + 2 * BM * LDK;  // [2][BN][LDK]
+
+    const int work = xcd_contiguous_work(blockIdx.x, P.perXcd);
+    if (work >= P.total) return;
+    const int nt = work % P.nTiles;
+    const int mt = (work / P.nTiles) % P.mTiles;
+    const int pos = work / (P.nTiles * P.mTiles);
+    const RunSet R = decode_position<OP>(P, pos);
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    // Global -> LDS staging: 8 threads cover one 32-float row chunk (128 B).
+    const int lr = tid >> 3, lc = (tid & 7) * 4;
+    const float *pa[PA], *pb[PB];
+#pragma unroll
+    for (int i = 0; i < PA; ++i) pa[i] = P.A + (long)min(m0 + lr + 32 * i, P.N - 1) * R.strideA + R.a0 + lc;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) pb[i] = P.B + (long)min(n0 + lr + 32 * i, R.NC - 1) * R.strideB + R.b0 + lc;
+
+    const int cpr = (R.L + KC - 1) / KC;  // chunks per run
+    const int T = R.nruns * cpr;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[PA], rb[PB];
+    auto gload = [&](int run, int ck) {
+        const long oa = run * R.aRun + ck * KC, ob = run * R.bRun + ck * KC;
+        const int valid = R.L - ck * KC - lc;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) ra[i] = load4<VEC>(pa[i] + oa, valid);
+#pragma unroll
+        for (int i = 0; i < PB; ++i) rb[i] = load4<VEC>(pb[i] + ob, valid);
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[(buf * BM + lr + 32 * i) * LDK + lc]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(&Bs[(buf * BN + lr + 32 * i) * LDK + lc]) = rb[i];
+    };
+
+    // MFMA fragments: lane l reads 4 consecutive k of row (l%32); the two lane
+    // halves take k-groups 4 apart, so one 16-byte read feeds 4 MFMAs.
+    const int frow = lane & 31, fk = (lane >> 5) * 4;
+    auto kstep = [&](const float *Ab, const float *Bb, int kk) {
+        float4 a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4 *>(Ab + i * 32 * LDK + kk * 8);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4 *>(Bb + j * 32 * LDK + kk * 8);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                acc[i][j] = mfma32(a[i].x, b[j].x, acc[i][j]);
+                acc[i][j] = mfma32(a[i].y, b[j].y, acc[i][j]);
+                acc[i][j] = mfma32(a[i].z, b[j].z, acc[i][j]);
+                acc[i][j] = mfma32(a[i].w, b[j].w, acc[i][j]);
+            }
+    };
+
+    int run = 0, ck = 0;
+    if (T > 0) {
+        gload(0, 0);
+        sstore(0);
+    }
+    __syncthreads();
+    for (int t = 0; t < T; ++t) {
+        const int buf = t & 1;
+        int nrun = run, nck = ck + 1;
+        if (nck == cpr) { nck = 0; ++nrun; }
+        const bool more = t + 1 < T;
+        if (more) gload(nrun, nck);
+
+        const float *Ab = As + (buf * BM + wm * TM * 32 + frow) * LDK + fk;
+        const float *Bb = Bs + (buf * BN + wn * TN * 32 + frow) * LDK + fk;
+        const int nk = (min(KC, R.L - ck * KC) + 7) >> 3;
+        if (nk == KC / 8) {
+#pragma unroll
+            for (int kk = 0; kk < KC / 8; ++kk) kstep(Ab, Bb, kk);
+        } else {
+            for (int kk = 0; kk < nk; ++kk) kstep(Ab, Bb, kk);
+        }
+
+        if (more) sstore(buf ^ 1);
+        __syncthreads();
+        run = nrun;
+        ck = nck;
+    }
+
+    // Every output element of the tile is stored, also when the trimmed range
+    // was empty (then it is +0.0).  32 lanes write 128 contiguous bytes.
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < P.N && col < R.NC) P.Out[(long)row * R.strideO + R.o0 + col] = acc[i][j][r];
+            }
+        }
+}
+
+}  // namespace cks

@@ -1,0 +1,99 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, validates arguments before touching the
+device, and its geometry helpers agree with the oracle's enumeration."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def cks():
+    from paper_2306_15951_amd import binding, build
+
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_lib()
+    binding.lib()
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cks.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cks_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(cks):
+    names = declared_symbols()
+    assert len(names) >= 14
+    L = ctypes.CDLL(cks.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(cks.EXPORTS) == names          # the binding covers the same set
+    for n in names:
+        assert hasattr(cks, n) or n in ("cks_strerror", "cks_last_hip_error")
+
+
+def test_out_dims_and_shape_errors(cks):
+    assert cks.cks_out_dims(224, 224, 7, 7, 2, 3) == (112, 112)
+    assert cks.cks_out_dims(7, 4, 3, 3, 1, 1) == (7, 4)
+    assert cks.cks_out_dims(8, 8, 3, 3, 2, 0) == (3, 3)
+    L = cks.lib()
+    assert L.cks_out_dims(2, 2, 5, 5, 1, 1, None, None) == cks.CKS_ERR_SHAPE
+    assert L.cks_out_dims(4, 4, 3, 3, 0, 1, None, None) == cks.CKS_ERR_SHAPE
+    assert L.cks_out_dims(4, 4, 3, 3, 1, -1, None, None) == cks.CKS_ERR_SHAPE
+    with pytest.raises(cks.CksError):
+        cks.cks_out_dims(2, 2, 5, 5, 1, 1)
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch(cks):
+    L = cks.lib()
+    good = (2, 4, 8, 8, 4, 3, 3, 1, 1)
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every call below must fail in validation
+    for fn in (L.cks_conv2d_fwd, L.cks_deconv2d, L.cks_dilated_conv2d_wgrad):
+        assert fn(None, fake, fake, *good, None, 0, None) == cks.CKS_ERR_NULL
+        assert fn(fake, None, fake, *good, None, 0, None) == cks.CKS_ERR_NULL
+        assert fn(fake, fake, None, *good, None, 0, None) == cks.CKS_ERR_NULL
+        for bad in ((0, 4, 8, 8, 4, 3, 3, 1, 1), (2, 4, 8, 8, 4, 3, 3, 0, 1), (2, 4, 8, 8, 4, 3, 3, 1, -1),
+                    (2, 4, 2, 8, 4, 5, 3, 1, 1), (2, 4, 8, 8, 0, 3, 3, 1, 1),
+                    (1 << 16, 1 << 10, 1 << 6, 1 << 6, 4, 3, 3, 1, 1)):      # 2^38 elements
+            assert fn(fake, fake, fake, *bad, None, 0, None) == cks.CKS_ERR_SHAPE
+    # KS-deconv always needs the split-kernel workspace
+    need = L.cks_deconv2d_workspace(*good)
+    assert need == cks.cks_kernel_split_bytes(4, 4, 3, 3, 1) == 4 * 4 * 3 * 3 * 4
+    assert L.cks_deconv2d(fake, fake, fake, *good, None, 0, None) == cks.CKS_ERR_WORKSPACE
+    assert L.cks_deconv2d(fake, fake, fake, *good, fake, need - 1, None) == cks.CKS_ERR_WORKSPACE
+    # Sk-dilated needs one slice of dW per segment when the contraction axis is split
+    big = (128, 64, 32, 32, 64, 3, 3, 1, 1)
+    gz = L.cks_dilated_conv2d_wgrad_segments(*big)
+    assert gz > 1
+    assert L.cks_dilated_conv2d_wgrad_workspace(*big) == 4 * gz * 64 * 9 * 64
+    assert L.cks_dilated_conv2d_wgrad(fake, fake, fake, *big, None, 0, None) == cks.CKS_ERR_WORKSPACE
+    assert L.cks_kernel_split(None, fake, 4, 4, 3, 3, 2, None) == cks.CKS_ERR_NULL
+    assert L.cks_kernel_split(fake, fake, 4, 4, 3, 3, 0, None) == cks.CKS_ERR_SHAPE
+    assert L.cks_filter_transpose(fake, None, 4, 4, 3, 3, None) == cks.CKS_ERR_NULL
+    assert L.cks_deconv2d_presplit(fake, fake, None, *good, None) == cks.CKS_ERR_NULL
+    assert L.cks_strerror(cks.CKS_ERR_WORKSPACE).decode().startswith("workspace")
+    assert L.cks_deconv2d_workspace(2, 4, 2, 8, 4, 5, 3, 1, 1) == 0
+
+
+def test_split_tensor_size_matches_the_paper_layout(cks):
+    # Algorithm 2 Stage 1: s * s * OC * ceil(FH/s) * ceil(FW/s) * IC elements
+    assert cks.cks_kernel_split_bytes(3, 5, 7, 7, 2) == 4 * 2 * 2 * 5 * 4 * 4 * 3
+    assert cks.cks_kernel_split_bytes(1, 1, 3, 3, 2) == 4 * 16      # Fig. 5: C is 2x2x2x2
+    assert cks.cks_kernel_split_bytes(2, 2, 1, 1, 3) == 4 * 9 * 4
+
+
+def test_useful_macs_agree_with_enumeration(cks, oracle):
+    from paper_2306_15951_amd import synth
+
+    for L in synth.LAYERS.values():
+        g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+        assert cks.cks_useful_macs(*g) == oracle.mac_counts(*g)["useful"], L.name
+    for g in [(1, 1, 4, 4, 1, 3, 3, 2, 1), (2, 3, 5, 8, 2, 4, 2, 3, 3), (1, 2, 3, 5, 2, 1, 1, 2, 0), (1, 1, 7, 4, 1, 5, 5, 1, 4)]:
+        assert cks.cks_useful_macs(*g) == oracle.mac_counts(*g)["useful"], g
+    assert 2 * cks.cks_useful_macs(1, 1, 4, 4, 1, 3, 3, 2, 1) == 50   # the paper's worked example
+    assert cks.cks_useful_macs(1, 1, 2, 2, 1, 5, 5, 1, 1) == -1

@@ -1,0 +1,280 @@
+"""GPU parity: every operator, through the C ABI, element by element against
+the CPU oracle on the same seeded inputs.
+
+Bars: bit-exact on small-integer inputs (all partial sums are exact in fp32);
+otherwise |gpu - oracle| <= 1e-5 * sum(|x||w|) per output element, the sum
+being the oracle applied to the absolute values of the same inputs.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def cks():
+    import torch
+    from paper_2306_15951_amd import binding
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def nan_like(shape):
+    import torch
+
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+
+def run_three(cks, L, X, W, dY):
+    """All three operators of layer L through the ABI.  Outputs start as NaN so
+    an element the kernels forget to write cannot pass."""
+    import torch
+
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+    OH, OW = cks.cks_out_dims(L.IH, L.IW, L.FH, L.FW, L.stride, L.padding)
+    Xd, Wd, dYd = dev(X), dev(W), dev(dY)
+    Y = nan_like((L.N, OH, OW, L.OC))
+    dX = nan_like((L.N, L.IH, L.IW, L.IC))
+    dW = nan_like((L.OC, L.FH, L.FW, L.IC))
+    ws1 = torch.full((max(cks.cks_deconv2d_workspace(*g) // 4, 1),), float("nan"), device="cuda")
+    ws2 = torch.full((max(cks.cks_dilated_conv2d_wgrad_workspace(*g) // 4, 1),), float("nan"), device="cuda")
+    cks.cks_conv2d_fwd(Xd, Wd, Y, L.stride, L.padding)
+    cks.cks_deconv2d(dYd, Wd, dX, L.stride, L.padding, ws1)
+    cks.cks_dilated_conv2d_wgrad(Xd, dYd, dW, L.stride, L.padding, ws2)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy(), dX.cpu().numpy(), dW.cpu().numpy()
+
+
+def oracle_three(oracle, L, X, W, dY, samples=None):
+    s = samples or (None, None, None)
+    return (oracle.conv_fwd(X, W, L.stride, L.padding, sample=s[0]),
+            oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding, sample=s[1]),
+            oracle.wgrad(X, dY, L.FH, L.FW, L.stride, L.padding, sample=s[2]))
+
+
+def assert_exact(got, want, what):
+    """Bitwise: same value and no negative zero."""
+    want32 = want.astype(np.float32)
+    assert np.array_equal(want32.astype(np.float64), want), "oracle value not representable: " + what
+    bad = got.view(np.uint32) != (want32 + np.float32(0)).view(np.uint32)
+    assert not bad.any(), "%s: %d of %d elements differ, first at %s" % (
+        what, bad.sum(), bad.size, np.argwhere(bad)[:3].tolist())
+
+
+def assert_close(got, want, bound, what):
+    err = np.abs(got.astype(np.float64) - want)
+    lim = TOL * bound + 1e-30
+    bad = ~(err <= lim)      # also catches NaN
+    assert not bad.any(), "%s: %d of %d elements out of tolerance, worst err/bound %.3g" % (
+        what, bad.sum(), bad.size, np.nanmax(err / np.maximum(bound, 1e-30)))
+
+
+def check_layer(cks, oracle, L, seed=0, kinds=("int", "normal"), samples=None):
+    from paper_2306_15951_amd import synth
+
+    for kind in kinds:
+        X, W, dY = synth.make_inputs(L, kind, seed)
+        got = run_three(cks, L, X, W, dY)
+        if samples is not None:
+            got = tuple(g.ravel()[s] for g, s in zip(got, samples))
+        want = oracle_three(oracle, L, X, W, dY, samples)
+        names = ["%s %s %s" % (L.name, kind, op) for op in ("conv2d_fwd", "deconv2d", "dilated_conv2d_wgrad")]
+        if kind == "int":
+            for g, w, nm in zip(got, want, names):
+                assert_exact(g, w, nm)
+        else:
+            bound = oracle_three(oracle, L, np.abs(X), np.abs(W), np.abs(dY), samples)
+            for g, w, b, nm in zip(got, want, bound, names):
+                assert_close(g, w, b, nm)
+
+
+def test_config0_uniform_and_integer(cks, oracle):
+    from paper_2306_15951_amd import synth
+
+    check_layer(cks, oracle, synth.LAYERS["cfg0"], kinds=("int", "uniform", "normal"))
+
+
+# (name, N, IC, IH, IW, OC, FH, FW, stride, padding): several tiles and ragged
+# tails in every GEMM dimension, both load paths (channel counts that are and
+# are not multiples of 4), non-square maps and filters, strides 1-3, padding
+# from 0 to beyond the filter, stride larger than the filter, remainder rows.
+MID = [
+    ("tiles_ragged", 150, 36, 9, 10, 72, 3, 3, 1, 1),
+    ("wide_channels", 70, 136, 6, 5, 200, 3, 3, 1, 1),
+    ("stride2_3x3", 130, 40, 11, 12, 68, 3, 3, 2, 1),
+    ("stride2_4x4", 66, 24, 10, 10, 36, 4, 4, 2, 1),
+    ("stride3_5x4", 40, 8, 13, 11, 12, 5, 4, 3, 2),
+    ("odd_channels", 33, 5, 9, 7, 7, 3, 3, 1, 1),
+    ("stem_like", 20, 3, 30, 28, 16, 7, 7, 2, 3),
+    ("odd_channels_s2", 9, 6, 8, 9, 10, 2, 3, 2, 0),
+    ("pad_ge_filter", 12, 4, 5, 6, 8, 2, 2, 1, 3),
+    ("stride_gt_filter", 10, 8, 9, 9, 4, 1, 1, 2, 0),
+    ("stride_gt_filter_p", 10, 4, 7, 8, 4, 2, 2, 3, 1),
+    ("one_by_one", 200, 48, 5, 5, 96, 1, 1, 1, 0),
+    ("remainder_rows", 16, 12, 8, 9, 20, 3, 3, 2, 0),
+    ("single_image", 1, 16, 12, 12, 16, 3, 3, 1, 1),
+    ("filter_covers_map", 8, 4, 3, 3, 4, 5, 5, 1, 2),
+    ("small_map_big_batch", 300, 20, 4, 4, 24, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("geo", MID, ids=[g[0] for g in MID])
+def test_midsize_geometries(cks, oracle, geo):
+    from paper_2306_15951_amd import synth
+
+    print("geometry", geo, flush=True)
+    check_layer(cks, oracle, synth.Layer(*geo), seed=100 + [g[0] for g in MID].index(geo[0]))
+
+
+def structured_samples(shape, rng, n_random):
+    """Random flat indices plus the corners / borders of every axis."""
+    idx = [rng.integers(0, int(np.prod(shape)), size=n_random)]
+    edges = [sorted({0, 1, d // 2, d - 2, d - 1} & set(range(d))) for d in shape]
+    grid = np.stack(np.meshgrid(*edges, indexing="ij"), -1).reshape(-1, len(shape))
+    idx.append(np.ravel_multi_index(grid.T, shape))
+    return np.unique(np.concatenate(idx))
+
+
+FULL = ["cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4a", "cfg4b"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_configs_sampled(cks, oracle, name):
+    """The benchmark layers at full size, in the launch configuration the
+    benchmark times.  The oracle evaluates a sample of output elements (random
+    ones plus the borders of every axis) one by one."""
+    from paper_2306_15951_amd import synth
+
+    L = synth.LAYERS[name]
+    print("layer", L, flush=True)
+    xs, ws, ys = synth.shapes(L)
+    rng = np.random.default_rng(17)
+    samples = (structured_samples(ys, rng, 20000), structured_samples(xs, rng, 20000),
+               structured_samples(ws, rng, 600))
+    check_layer(cks, oracle, L, samples=samples)
+
+
+def test_full_size_cfg1_every_element(cks, oracle):
+    """One benchmark layer compared in full, not sampled (forward and input gradient)."""
+    from paper_2306_15951_amd import synth
+
+    L = synth.LAYERS["cfg1"]
+    X, W, dY = synth.make_inputs(L, "int", 3)
+    Y, dX, dW = run_three(cks, L, X, W, dY)
+    assert_exact(Y, oracle.conv_fwd(X, W, L.stride, L.padding), "cfg1 fwd full")
+    assert_exact(dX, oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding), "cfg1 deconv full")
+
+
+def test_stage_entry_points(cks, oracle):
+    """Stage 1 (kernel split) and the filter transposition against the oracle's
+    data-movement definitions; Stage 2&3 on a pre-split filter equals the fused call."""
+    import torch
+
+    rng = np.random.default_rng(5)
+    for (OC, FH, FW, IC, s) in [(40, 3, 3, 36, 2), (7, 7, 7, 3, 2), (33, 4, 4, 65, 2), (8, 5, 3, 12, 3), (16, 3, 3, 16, 1), (4, 1, 1, 4, 2)]:
+        W = rng.standard_normal((OC, FH, FW, IC)).astype(np.float32)
+        Wd = dev(W)
+        Cs = nan_like((s, s, IC, -(-FH // s), -(-FW // s), OC))
+        cks.cks_kernel_split(Wd, Cs, s)
+        Wt = nan_like((FH, FW, IC, OC))
+        cks.cks_filter_transpose(Wd, Wt)
+        torch.cuda.synchronize()
+        # the library keeps the paper's 6-D tensor with the two channel axes exchanged
+        want = np.transpose(oracle.kernel_split(W, s), (0, 1, 5, 3, 4, 2))
+        assert np.array_equal(Cs.cpu().numpy().view(np.uint32), want.view(np.uint32)), (OC, FH, FW, IC, s)
+        assert np.array_equal(Wt.cpu().numpy(), oracle.filter_transpose(W))
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer("presplit", 40, 12, 9, 8, 20, 3, 3, 2, 1)
+    X, W, dY = synth.make_inputs(L, "int", 1)
+    Cs = nan_like((2, 2, L.IC, 2, 2, L.OC))
+    dX = nan_like((L.N, L.IH, L.IW, L.IC))
+    cks.cks_kernel_split(dev(W), Cs, 2)
+    cks.cks_deconv2d_presplit(dev(dY), Cs, dX, L.FH, L.FW, 2, 1)
+    torch.cuda.synchronize()
+    assert_exact(dX.cpu().numpy(), oracle.deconv(dY, W, L.IH, L.IW, 2, 1), "presplit")
+
+
+def test_no_write_outside_outputs_and_unaligned_pointers(cks, oracle):
+    """Outputs, inputs and workspaces sit inside guard bands; offsets of one
+    float make every pointer 4-byte aligned only (scalar load path)."""
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer("guards", 37, 8, 7, 9, 12, 3, 3, 2, 1)
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+    X, W, dY = synth.make_inputs(L, "int", 2)
+    OH, OW = cks.cks_out_dims(L.IH, L.IW, L.FH, L.FW, L.stride, L.padding)
+    want = oracle_three(oracle, L, X, W, dY)
+    SENT = 12345.0
+    for off in (64, 1):
+        def guarded(n):
+            buf = torch.full((n + 2 * off,), SENT, dtype=torch.float32, device="cuda")
+            return buf, buf[off:off + n]
+
+        def inside(a):
+            buf, v = guarded(a.size)
+            v.copy_(dev(a).reshape(-1))
+            return v.view(a.shape)
+
+        Xd, Wd, dYd = inside(X), inside(W), inside(dY)
+        bY, vY = guarded(L.N * OH * OW * L.OC)
+        bX, vX = guarded(X.size)
+        bW, vW = guarded(W.size)
+        b1, v1 = guarded(cks.cks_deconv2d_workspace(*g) // 4)
+        b2, v2 = guarded(max(cks.cks_dilated_conv2d_wgrad_workspace(*g) // 4, 1))
+        cks.cks_conv2d_fwd(Xd, Wd, vY.view(L.N, OH, OW, L.OC), L.stride, L.padding)
+        cks.cks_deconv2d(dYd, Wd, vX.view(X.shape), L.stride, L.padding, v1)
+        cks.cks_dilated_conv2d_wgrad(Xd, dYd, vW.view(W.shape), L.stride, L.padding, v2)
+        torch.cuda.synchronize()
+        for b, v, w, nm in ((bY, vY, want[0], "Y"), (bX, vX, want[1], "dX"), (bW, vW, want[2], "dW")):
+            assert_exact(v.cpu().numpy().reshape(w.shape), w, "%s off=%d" % (nm, off))
+        for b in (bY, bX, bW, b1, b2):
+            h = b.cpu().numpy()
+            assert np.all(h[:off] == SENT) and np.all(h[-off:] == SENT), "guard band overwritten (off=%d)" % off
+
+
+def test_wgrad_is_reproducible_bit_for_bit(cks):
+    """The split contraction axis is reduced in a fixed order."""
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.LAYERS["cfg2"]
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+    assert cks.cks_dilated_conv2d_wgrad_segments(*g) > 1
+    X, W, dY = synth.make_inputs(L, "normal", 4)
+    Xd, dYd = dev(X), dev(dY)
+    ws = torch.empty(cks.cks_dilated_conv2d_wgrad_workspace(*g) // 4, device="cuda")
+    outs = []
+    for _ in range(3):
+        dW = nan_like(W.shape)
+        ws.fill_(float("nan"))
+        cks.cks_dilated_conv2d_wgrad(Xd, dYd, dW, L.stride, L.padding, ws)
+        torch.cuda.synchronize()
+        outs.append(dW.cpu().numpy().view(np.uint32))
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_errors_on_device(cks):
+    import torch
+
+    X = torch.zeros((2, 8, 8, 4), device="cuda")
+    W = torch.zeros((4, 3, 3, 4), device="cuda")
+    dX = torch.zeros_like(X)
+    dY = torch.zeros((2, 8, 8, 4), device="cuda")
+    small = torch.zeros(3, device="cuda")
+    with pytest.raises(cks.CksError) as e:
+        cks.cks_deconv2d(dY, W, dX, 1, 1, small)
+    assert e.value.status == cks.CKS_ERR_WORKSPACE
+    with pytest.raises(ValueError):
+        cks.cks_conv2d_fwd(X, W, torch.zeros((2, 7, 8, 4), device="cuda"), 1, 1)
