@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the C-K-S conv-layer hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch of a layer:
+ConvV2 forward, KS-deconv-V2 input gradient (kernel split + Stage 2&3) and
+Sk-dilated-V2 filter gradient (segments + reduction), inputs resident in HBM.
+Prints ONE JSON line: useful (zero-free) TFLOP/s of the step, the roofline of
+the dominant kernel measured with events on the launch stream, and the CPU
+oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg1] [--all]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak
+METRIC = "useful TFLOPS per operator (ConvV2 / KS-deconv / Sk-dilated), % fp32 MFMA peak"
+
+
+def describe(L):
+    return ("%s: N=%d C=%d H=W=%dx%d OC=%d %dx%d stride %d pad %d, fp32 NHWC; X,dY~N(0,1), W He-normal"
+            % (L.name, L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding))
+
+
+class LayerBench:
+    """Device buffers of one layer and the calls of its hot path."""
+
+    def __init__(self, L, seed=0):
+        import torch
+        from paper_2306_15951_amd import binding as cks
+        from paper_2306_15951_amd import synth
+
+        self.L, self.cks, self.torch = L, cks, torch
+        self.g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+        self.host = synth.make_inputs(L, "normal", seed)
+        X, W, dY = self.host
+        d = "cuda:0"
+        self.X, self.W, self.dY = (torch.from_numpy(a).to(d) for a in (X, W, dY))
+        self.Y = torch.empty_like(self.dY)
+        self.dX = torch.empty_like(self.X)
+        self.dW = torch.empty_like(self.W)
+        self.gz = cks.cks_dilated_conv2d_wgrad_segments(*self.g)
+        self.ws_deconv = torch.empty(max(cks.cks_deconv2d_workspace(*self.g) // 4, 1), device=d)
+        self.ws_wgrad = torch.empty(max(cks.cks_dilated_conv2d_wgrad_workspace(*self.g) // 4, 1), device=d)
+        s = L.stride
+        self.Cs = torch.empty((s, s, L.IC, -(-L.FH // s), -(-L.FW // s), L.OC), device=d)
+        self.part = torch.empty((self.gz, L.OC, L.FH, L.FW, L.IC), device=d)
+        self.useful_flops = 2 * cks.cks_useful_macs(*self.g)
+
+    # the three operators as a user calls them
+    def fwd(self):
+        self.cks.cks_conv2d_fwd(self.X, self.W, self.Y, self.L.stride, self.L.padding)
+
+    def deconv(self):
+        self.cks.cks_deconv2d(self.dY, self.W, self.dX, self.L.stride, self.L.padding, self.ws_deconv)
+
+    def wgrad(self):
+        self.cks.cks_dilated_conv2d_wgrad(self.X, self.dY, self.dW, self.L.stride, self.L.padding, self.ws_wgrad)
+
+    def step(self):
+        self.fwd()
+        self.deconv()
+        self.wgrad()
+
+    # single kernels (stage entry points)
+    def k_split(self):
+        self.cks.cks_kernel_split(self.W, self.Cs, self.L.stride)
+
+    def k_deconv_main(self):
+        self.cks.cks_deconv2d_presplit(self.dY, self.Cs, self.dX, self.L.FH, self.L.FW, self.L.stride, self.L.padding)
+
+    def k_wgrad_main(self):
+        self.cks.cks_dilated_conv2d_wgrad_partials(self.X, self.dY, self.part, self.L.FH, self.L.FW,
+                                                   self.L.stride, self.L.padding)
+
+    def k_reduce(self):
+        self.cks.cks_reduce_partials(self.part, self.dW)
+
+    def time_ms(self, fn, iters, warmup):
+        """Average milliseconds per call: events on the stream the library launches on."""
+        torch = self.torch
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()          # torch's current stream == the stream handed to the library
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(L, host, useful_flops, budget_s=6.0):
+    """The oracle as it stands, on a random sample of outputs of each operator,
+    sized from a short calibration so that each operator takes about budget_s."""
+    import numpy as np
+    import oracle
+
+    X, W, dY = host
+    rng = np.random.default_rng(1)
+    ops = (("conv_fwd", dY.size, lambda sm: oracle.conv_fwd(X, W, L.stride, L.padding, sample=sm)),
+           ("deconv", X.size, lambda sm: oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding, sample=sm)),
+           ("wgrad", W.size, lambda sm: oracle.wgrad(X, dY, L.FH, L.FW, L.stride, L.padding, sample=sm)))
+    flops = secs = 0.0
+    parts = []
+    for name, size, fn in ops:
+        n0 = max(min(size // 1000, 2000), 16)
+        t = time.time(); fn(rng.integers(0, size, n0)); t0 = time.time() - t    # includes materialising the zeros
+        t = time.time(); fn(rng.integers(0, size, 4 * n0)); t1 = time.time() - t
+        per = max((t1 - t0) / (3 * n0), 1e-9)
+        n = int(min(size, max(n0, (budget_s - min(t0, budget_s / 2)) / per)))
+        t = time.time(); fn(rng.integers(0, size, n)); dt = time.time() - t
+        flops += useful_flops * n / size
+        secs += dt
+        parts.append("%s %d of %d outputs in %.2fs" % (name, n, size, dt))
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "; ".join(parts) + " (random output elements, useful FLOPs pro rata, "
+                      "time includes building the padded / zero-inserted tensors)"}
+
+
+def bench_layer(L, steps, warmup, with_kernels=True):
+    B = LayerBench(L)
+    out = {"useful_gflop_per_operator": B.useful_flops / 1e9, "segments_G_Z": B.gz}
+    ms_step = B.time_ms(B.step, steps, warmup)
+    out["ms_per_step"] = ms_step
+    out["step_tflops"] = 3 * B.useful_flops / ms_step / 1e9
+    ops = {}
+    for name, fn in (("conv2d_fwd", B.fwd), ("deconv2d", B.deconv), ("dilated_conv2d_wgrad", B.wgrad)):
+        ms = B.time_ms(fn, steps, warmup)
+        tf = B.useful_flops / ms / 1e9
+        ops[name] = {"ms": ms, "useful_tflops": tf, "pct_fp32_mfma_peak": 100 * tf / PEAK_FP32_MFMA_TFLOPS}
+    out["operators"] = ops
+    if with_kernels:
+        B.k_split(); B.k_wgrad_main()
+        ker = {}
+        for name, fn in (("rowrun_gemm<fwd>", B.fwd), ("pack_filter<split>", B.k_split),
+                         ("rowrun_gemm<deconv>", B.k_deconv_main), ("pixel_gemm", B.k_wgrad_main),
+                         ("reduce_slices", B.k_reduce)):
+            ker[name] = B.time_ms(fn, steps, warmup)
+        out["kernel_ms"] = ker
+    return B, out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="cfg1")
+    ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (extra JSON field)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2306_15951_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    L = synth.LAYERS[a.config]
+    B, r = bench_layer(L, a.steps, a.warmup)
+
+    # dominant kernel of the step = the main kernel with the longest average launch
+    mains = {k: r["kernel_ms"][k] for k in ("rowrun_gemm<fwd>", "rowrun_gemm<deconv>", "pixel_gemm")}
+    dom = max(mains, key=mains.get)
+    achieved = B.useful_flops / mains[dom] / 1e9
+    line = {
+        "metric": METRIC, "value": r["step_tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": describe(L), "step": "conv2d_fwd + deconv2d + dilated_conv2d_wgrad",
+                   "useful_gflop_per_operator": r["useful_gflop_per_operator"], "segments_G_Z": r["segments_G_Z"]},
+        "pct_fp32_mfma_peak": 100 * r["step_tflops"] / PEAK_FP32_MFMA_TFLOPS,
+        "operators": r["operators"], "kernel_ms": r["kernel_ms"],
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "all_main_kernels": {k: B.useful_flops / v / 1e9 for k, v in mains.items()}},
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(L, B.host, B.useful_flops)
+    if a.all:
+        others = {}
+        for name in synth.LAYERS:
+            if name in (a.config, "cfg0"):
+                continue
+            del B
+            torch.cuda.empty_cache()
+            B, rr = bench_layer(synth.LAYERS[name], max(a.steps // 4, 10), max(a.warmup // 2, 5))
+            others[name] = rr
+        line["other_configs"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -53,7 +53,7 @@ typedef enum {
                                  than the padded input, or a tensor of 2^31 or more elements */
     CKS_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than the *_workspace() size */
     CKS_ERR_HIP = -4,         /* a HIP runtime call failed; see cks_last_hip_error() */
-    CKS_ERR_UNSUPPORTED = -5  /* valid but not implemented (stride > 64) */
+    CKS_ERR_UNSUPPORTED = -5  /* reserved: valid geometry without an implementation */
 } cks_status;
 
 /* Output size of Eq. (1).  OH, OW may be NULL.  Returns CKS_ERR_SHAPE if the
@@ -122,6 +122,18 @@ int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, in
 /* Number of segments the contraction axis of cks_dilated_conv2d_wgrad is split
  * into for this geometry (the paper's G_Z); 0 on bad geometry. */
 int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+
+/* The "map" half of Sk-dilated-V2 (Section IV.C): segment z of the contraction
+ * axis writes its partial filter gradient to part[z], with
+ * part [G_Z][OC][FH][FW][C], G_Z = cks_dilated_conv2d_wgrad_segments(...).
+ * Every element of part is written. */
+int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *part,
+                                      int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                                      void *stream);
+
+/* The "reduce" half: dW[e] = part[0][e] + part[1][e] + ... in that order,
+ * for e < elems (= OC*FH*FW*C), segments >= 1. */
+int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream);
 
 const char *cks_strerror(int status);
 int cks_last_hip_error(void);

@@ -54,6 +54,8 @@ def _load():
         lib.cko_kernel_split.restype = ctypes.c_int
         lib.cko_mac_counts.argtypes = [ip] + geo
         lib.cko_mac_counts.restype = ctypes.c_int
+        lib.cko_num_threads.argtypes = []
+        lib.cko_num_threads.restype = ctypes.c_int
         lib.cko_out_dim.argtypes = [ctypes.c_int] * 4
         lib.cko_out_dim.restype = ctypes.c_int
         _lib = lib
@@ -170,3 +172,8 @@ def mac_counts(N, IC, IH, IW, OC, FH, FW, stride, padding):
     _check(_load().cko_mac_counts(c.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                                   N, IC, IH, IW, OC, FH, FW, stride, padding))
     return dict(dense=int(c[0]), useful=int(c[1]), nominal_deconv=int(c[2]), nominal_dilated=int(c[3]))
+
+
+def num_threads():
+    """OpenMP threads the operators run on."""
+    return _load().cko_num_threads()

@@ -27,6 +27,8 @@ _PROTOTYPES = {
     "cks_conv2d_fwd": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p], ctypes.c_int),
     "cks_deconv2d": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p], ctypes.c_int),
     "cks_dilated_conv2d_wgrad": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p], ctypes.c_int),
+    "cks_dilated_conv2d_wgrad_partials": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p], ctypes.c_int),
+    "cks_reduce_partials": ([ctypes.c_void_p] * 2 + [ctypes.c_int64, ctypes.c_int, ctypes.c_void_p], ctypes.c_int),
     "cks_kernel_split_bytes": ([ctypes.c_int] * 5, ctypes.c_size_t),
     "cks_kernel_split": ([ctypes.c_void_p] * 2 + [ctypes.c_int] * 5 + [ctypes.c_void_p], ctypes.c_int),
     "cks_deconv2d_presplit": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p], ctypes.c_int),
@@ -184,3 +186,22 @@ def cks_filter_transpose(Wt, Wout):
     _check(lib().cks_filter_transpose(_ptr(Wt, "Wt"), _ptr(Wout, "Wout", (FH, FW, C, OC)), C, OC, FH, FW, _stream()),
            "cks_filter_transpose")
     return Wout
+
+
+def cks_dilated_conv2d_wgrad_partials(X, dY, part, FH, FW, stride, padding):
+    """part[G_Z,OC,FH,FW,C] <- per-segment partial filter gradients."""
+    N, H, W, C = X.shape
+    OC = dY.shape[3]
+    OH, OW = cks_out_dims(H, W, FH, FW, stride, padding)
+    gz = cks_dilated_conv2d_wgrad_segments(N, C, H, W, OC, FH, FW, stride, padding)
+    _check(lib().cks_dilated_conv2d_wgrad_partials(_ptr(X, "X"), _ptr(dY, "dY", (N, OH, OW, OC)),
+                                                   _ptr(part, "part", (gz, OC, FH, FW, C)),
+                                                   N, C, H, W, OC, FH, FW, stride, padding, _stream()),
+           "cks_dilated_conv2d_wgrad_partials")
+    return part
+
+
+def cks_reduce_partials(part, dW):
+    _check(lib().cks_reduce_partials(_ptr(part, "part"), _ptr(dW, "dW", tuple(part.shape[1:])),
+                                     dW.numel(), part.shape[0], _stream()), "cks_reduce_partials")
+    return dW

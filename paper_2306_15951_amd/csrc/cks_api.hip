@@ -284,6 +284,45 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
     return cks_deconv2d_presplit(dY, (const float *)ws, dX, N, C, H, W, OC, FH, FW, stride, padding, stream);
 }
 
+int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *part,
+                                      int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                                      void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (rc != CKS_OK) return rc;
+    if (!X || !dY || !part) return CKS_ERR_NULL;
+    const WgradPlan w = plan_wgrad(g);
+    const long long total = (long long)w.GZ * FH * FW * w.mTiles * w.nTiles;
+    if (!fits_i31(total + kXcds)) return CKS_ERR_SHAPE;
+
+    PixelGemmParams P{};
+    P.X = X; P.dY = dY; P.Out = part;
+    P.N = N; P.IC = C; P.IH = H; P.IW = W; P.OC = OC; P.OH = g.OH; P.OW = g.OW;
+    P.FH = FH; P.FW = FW; P.s = stride; P.p = padding;
+    P.GZ = w.GZ; P.mTiles = w.mTiles; P.nTiles = w.nTiles;
+    P.total = (int)total;
+    P.perXcd = (P.total + kXcds - 1) / kXcds;
+    P.sliceElems = (long)OC * FH * FW * C;
+    const bool veca = (OC % 4 == 0) && aligned16(dY);
+    const bool vecb = (C % 4 == 0) && aligned16(X);
+    hipStream_t st = (hipStream_t)stream;
+    if (w.bm == 128 && w.bn == 128) return launch_pixel<128, 128>(P, veca, vecb, st);
+    if (w.bm == 128 && w.bn == 64) return launch_pixel<128, 64>(P, veca, vecb, st);
+    if (w.bm == 64 && w.bn == 128) return launch_pixel<64, 128>(P, veca, vecb, st);
+    return launch_pixel<64, 64>(P, veca, vecb, st);
+}
+
+int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream)
+{
+    if (elems <= 0 || segments < 1 || !fits_i31(elems)) return CKS_ERR_SHAPE;
+    if (!part || !dW) return CKS_ERR_NULL;
+    hipLaunchKernelGGL(reduce_slices, dim3((unsigned)((elems + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       (hipStream_t)stream, part, dW, (long)elems, segments);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CKS_OK : hip_fail(e);
+}
+
 int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
                              int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
                              void *ws, size_t ws_bytes, void *stream)
@@ -292,32 +331,14 @@ int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
     int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
     if (rc != CKS_OK) return rc;
     if (!X || !dY || !dW) return CKS_ERR_NULL;
-    const WgradPlan w = plan_wgrad(g);
+    const int GZ = plan_wgrad(g).GZ;
     const long slice = (long)OC * FH * FW * C;
-    if (w.GZ > 1 && (!ws || ws_bytes < sizeof(float) * (size_t)w.GZ * slice)) return CKS_ERR_WORKSPACE;
-    const long long total = (long long)w.GZ * FH * FW * w.mTiles * w.nTiles;
-    if (!fits_i31(total + kXcds)) return CKS_ERR_SHAPE;
-
-    PixelGemmParams P{};
-    P.X = X; P.dY = dY; P.Out = w.GZ > 1 ? (float *)ws : dW;
-    P.N = N; P.IC = C; P.IH = H; P.IW = W; P.OC = OC; P.OH = g.OH; P.OW = g.OW;
-    P.FH = FH; P.FW = FW; P.s = stride; P.p = padding;
-    P.GZ = w.GZ; P.mTiles = w.mTiles; P.nTiles = w.nTiles;
-    P.total = (int)total;
-    P.perXcd = (P.total + kXcds - 1) / kXcds;
-    P.sliceElems = slice;
-    const bool veca = (OC % 4 == 0) && aligned16(dY);
-    const bool vecb = (C % 4 == 0) && aligned16(X);
-    hipStream_t st = (hipStream_t)stream;
-    if (w.bm == 128 && w.bn == 128) rc = launch_pixel<128, 128>(P, veca, vecb, st);
-    else if (w.bm == 128 && w.bn == 64) rc = launch_pixel<128, 64>(P, veca, vecb, st);
-    else if (w.bm == 64 && w.bn == 128) rc = launch_pixel<64, 128>(P, veca, vecb, st);
-    else rc = launch_pixel<64, 64>(P, veca, vecb, st);
-    if (rc != CKS_OK || w.GZ == 1) return rc;
-    hipLaunchKernelGGL(reduce_slices, dim3((unsigned)((slice + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                       (const float *)ws, dW, slice, w.GZ);
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? CKS_OK : hip_fail(e);
+    if (GZ == 1)  // one segment: its "partial" result is the result
+        return cks_dilated_conv2d_wgrad_partials(X, dY, dW, N, C, H, W, OC, FH, FW, stride, padding, stream);
+    if (!ws || ws_bytes < sizeof(float) * (size_t)GZ * slice) return CKS_ERR_WORKSPACE;
+    rc = cks_dilated_conv2d_wgrad_partials(X, dY, (float *)ws, N, C, H, W, OC, FH, FW, stride, padding, stream);
+    if (rc != CKS_OK) return rc;
+    return cks_reduce_partials((const float *)ws, dW, slice, GZ, stream);
 }
 
 const char *cks_strerror(int status)
