@@ -4,6 +4,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+#include <cstdlib>
+
 #include "cks_pack.h"
 #include "cks_pixel_gemm.h"
 #include "cks_rowrun_gemm.h"
@@ -58,38 +61,46 @@ int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st)
 // ---------------------------------------------------------------- ConvV2 / KS-deconv Stage 2&3
 
 template <int OP, int BM, int BN, int WM, int WN>
-int launch_rowrun(RowRunParams P, int positions, int rows, int cols, bool vec, hipStream_t st)
+int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
 {
     P.mTiles = (rows + BM - 1) / BM;
     P.nTiles = (cols + BN - 1) / BN;
-    const long long total = (long long)positions * P.mTiles * P.nTiles;
-    if (!fits_i31(total + kXcds)) return CKS_ERR_SHAPE;
+    const long long items = (long long)P.itemsH * P.itemsW;
+    const long long total = items * P.mTiles * P.nTiles;
+    // bands: at least four per die if there are enough items, at most one row of items each
+    long long g = items / (4 * kXcds);
+    g = g < 1 ? 1 : (g > P.itemsW ? P.itemsW : g);
+    const long long bandBlocks = g * P.mTiles * P.nTiles;
+    const long long bands = (total + bandBlocks - 1) / bandBlocks;
+    const long long blocks = (bands + kXcds - 1) / kXcds * kXcds * bandBlocks;
+    if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
     P.total = (int)total;
-    P.perXcd = (P.total + kXcds - 1) / kXcds;
-    const int blocks = P.perXcd * kXcds;
+    P.bandBlocks = (int)bandBlocks;
     const size_t lds = rowrun_lds_bytes<BM, BN>();
-    if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, true>, P, blocks, lds, st);
-    return launch(rowrun_gemm<OP, BM, BN, WM, WN, false>, P, blocks, lds, st);
+    if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, true>, P, (int)blocks, lds, st);
+    return launch(rowrun_gemm<OP, BM, BN, WM, WN, false>, P, (int)blocks, lds, st);
 }
 
 template <int OP>
-int dispatch_rowrun(const RowRunParams &P, int positions, int rows, int cols, bool vec, hipStream_t st)
+int dispatch_rowrun(const RowRunParams &P, int rows, int cols, bool vec, hipStream_t st)
 {
+    const long long positions = (long long)P.itemsH * P.itemsW;
     // rows = batch, cols = output channels of this operator.  Prefer the
     // largest tile that still yields at least two workgroups per compute unit.
     int bm = rows >= 96 ? 128 : 64;
     int bn = cols >= 96 ? 128 : (cols >= 48 ? 64 : 32);
     if (bn == 32) bm = 128;
-    auto blocks = [&](int m, int n) { return (long long)positions * ((rows + m - 1) / m) * ((cols + n - 1) / n); };
+    auto blocks = [&](int m, int n) { return positions * ((rows + m - 1) / m) * ((cols + n - 1) / n); };
     if (bm == 128 && bn == 128 && blocks(bm, bn) < 2 * kCUs) bn = 64;
     if (bm == 128 && bn == 64 && blocks(bm, bn) < 2 * kCUs) bm = 64;
-    if (bm == 128 && bn == 128) return launch_rowrun<OP, 128, 128, 2, 2>(P, positions, rows, cols, vec, st);
-    if (bm == 128 && bn == 64) return launch_rowrun<OP, 128, 64, 2, 2>(P, positions, rows, cols, vec, st);
-    if (bm == 64 && bn == 128) return launch_rowrun<OP, 64, 128, 2, 2>(P, positions, rows, cols, vec, st);
-    if (bm == 64 && bn == 64) return launch_rowrun<OP, 64, 64, 2, 2>(P, positions, rows, cols, vec, st);
-    return launch_rowrun<OP, 128, 32, 4, 1>(P, positions, rows, cols, vec, st);
+    if (bm == 128 && bn == 128) return launch_rowrun<OP, 128, 128, 2, 2>(P, rows, cols, vec, st);
+    if (bm == 128 && bn == 64) return launch_rowrun<OP, 128, 64, 2, 2>(P, rows, cols, vec, st);
+    if (bm == 64 && bn == 128) return launch_rowrun<OP, 64, 128, 2, 2>(P, rows, cols, vec, st);
+    if (bm == 64 && bn == 64) return launch_rowrun<OP, 64, 64, 2, 2>(P, rows, cols, vec, st);
+    return launch_rowrun<OP, 128, 32, 4, 1>(P, rows, cols, vec, st);
 }
 
+template <int OP>
 RowRunParams rowrun_params(const Geo &g, const float *A, const float *B, float *Out)
 {
     RowRunParams P{};
@@ -98,6 +109,16 @@ RowRunParams rowrun_params(const Geo &g, const float *A, const float *B, float *
     P.FH = g.FH; P.FW = g.FW; P.s = g.s; P.p = g.p;
     P.CHp = (g.FH + g.s - 1) / g.s;
     P.CWp = (g.FW + g.s - 1) / g.s;
+    if (OP == OP_FWD) {
+        P.itemsH = g.OH; P.itemsW = g.OW;
+        P.rotH = ((g.p + g.s - 1) / g.s) % g.OH;          // output rows whose window starts in the padding
+        P.rotW = ((g.p + g.s - 1) / g.s) % g.OW;
+    } else {
+        P.itemsH = g.H; P.itemsW = g.W;
+        const int th = g.FH - 1 - g.p > 0 ? g.FH - 1 - g.p : 0, tw = g.FW - 1 - g.p > 0 ? g.FW - 1 - g.p : 0;
+        P.rotH = ((th + g.s - 1) / g.s) % g.H;            // positions per class whose dY window starts above row 0
+        P.rotW = ((tw + g.s - 1) / g.s) % g.W;
+    }
     return P;
 }
 
@@ -124,43 +145,58 @@ int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int 
 // ---------------------------------------------------------------- Sk-dilated
 
 struct WgradPlan {
-    int bm, bn, mTiles, nTiles, GZ;
+    int variant, bm, bn, mTiles, nTiles, GZ;
 };
 
-// G_Z: enough segments that the grid has about four workgroups per compute
-// unit, but never segments shorter than 512 pixels (Section IV.C: the number
-// of segments trades parallelism against the memory for partial sums).
+// Tile variants of pixel_gemm: {BM, BN, KC, WAVES_M, WAVES_N, WAVES_K}
+constexpr int kWgradVariants[][6] = {
+    {128, 128, 16, 2, 2, 1},  // 0
+    {128, 64, 32, 2, 1, 2},   // 1
+    {64, 128, 32, 1, 2, 2},   // 2
+    {64, 64, 32, 1, 1, 4},    // 3
+    {64, 64, 16, 2, 2, 1},    // 4
+    {128, 64, 16, 2, 2, 1},   // 5
+    {64, 128, 16, 2, 2, 1},   // 6
+};
+
+// G_Z: enough segments that the grid has about `target` workgroups, but never
+// segments shorter than 256 pixels (Section IV.C: the number of segments trades
+// parallelism against the memory for partial sums).
 WgradPlan plan_wgrad(const Geo &g)
 {
     WgradPlan w;
-    w.bm = g.OC >= 96 ? 128 : 64;
-    w.bn = g.C >= 96 ? 128 : 64;
+    const bool bigM = g.OC >= 96, bigN = g.C >= 96;
+    w.variant = bigM && bigN ? 0 : (bigM ? 5 : (bigN ? 6 : 4));
+    long long gz_override = 0;
+    if (const char *t = getenv("CKS_TUNE_WGRAD")) {   // "variant[,G_Z]" -- for tuning experiments
+        int v = -1, z = 0;
+        if (sscanf(t, "%d,%d", &v, &z) >= 1 && v >= 0 && v < 7) w.variant = v;
+        gz_override = z;
+    }
+    w.bm = kWgradVariants[w.variant][0];
+    w.bn = kWgradVariants[w.variant][1];
     w.mTiles = (g.OC + w.bm - 1) / w.bm;
     w.nTiles = (g.C + w.bn - 1) / w.bn;
-    long long tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
-    if (w.bm == 128 && w.bn == 128 && tiles < kCUs / 2) {
-        w.bn = 64;
-        w.nTiles = (g.C + 63) / 64;
-        tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
-    }
+    const long long tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
     const long long K = (long long)g.N * g.OH * g.OW;
     long long gz = (4LL * kCUs + tiles - 1) / tiles;
-    gz = gz < K / 512 ? gz : K / 512;
+    gz = gz < K / 256 ? gz : K / 256;
+    if (gz_override > 0) gz = gz_override;
     if (gz < 1) gz = 1;
-    if (gz > 256) gz = 256;
+    if (gz > 512) gz = 512;
     w.GZ = (int)gz;
     return w;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int KC, int WM, int WN, int WK>
 int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
 {
-    const size_t lds = pixel_lds_bytes<BM, BN>();
+    const size_t lds = pixel_lds_bytes<BM, BN, KC>();
     const int blocks = P.perXcd * kXcds;
-    if (veca && vecb) return launch(pixel_gemm<BM, BN, 2, 2, true, true>, P, blocks, lds, st);
-    if (veca) return launch(pixel_gemm<BM, BN, 2, 2, true, false>, P, blocks, lds, st);
-    if (vecb) return launch(pixel_gemm<BM, BN, 2, 2, false, true>, P, blocks, lds, st);
-    return launch(pixel_gemm<BM, BN, 2, 2, false, false>, P, blocks, lds, st);
+    if (veca && vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
+    if (veca) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
+    if (vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, true>, P, blocks, lds, st);
+    return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, false>, P, blocks, lds, st);
 }
 
 }  // namespace
@@ -237,7 +273,7 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
     if (rc != CKS_OK) return rc;
     if (!X || !Wt || !Y) return CKS_ERR_NULL;
     const bool vec = (C % 4 == 0) && aligned16(X) && aligned16(Wt);
-    return dispatch_rowrun<OP_FWD>(rowrun_params(g, X, Wt, Y), g.OH * g.OW, N, OC, vec, (hipStream_t)stream);
+    return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), N, OC, vec, (hipStream_t)stream);
 }
 
 int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream)
@@ -266,7 +302,7 @@ int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
     if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!dY || !Cs || !dX) return CKS_ERR_NULL;
     const bool vec = (OC % 4 == 0) && aligned16(dY) && aligned16(Cs);
-    return dispatch_rowrun<OP_DECONV>(rowrun_params(g, dY, Cs, dX), H * W, N, C, vec, (hipStream_t)stream);
+    return dispatch_rowrun<OP_DECONV>(rowrun_params<OP_DECONV>(g, dY, Cs, dX), N, C, vec, (hipStream_t)stream);
 }
 
 int cks_deconv2d(const float *dY, const float *Wt, float *dX,
@@ -307,10 +343,15 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
     const bool veca = (OC % 4 == 0) && aligned16(dY);
     const bool vecb = (C % 4 == 0) && aligned16(X);
     hipStream_t st = (hipStream_t)stream;
-    if (w.bm == 128 && w.bn == 128) return launch_pixel<128, 128>(P, veca, vecb, st);
-    if (w.bm == 128 && w.bn == 64) return launch_pixel<128, 64>(P, veca, vecb, st);
-    if (w.bm == 64 && w.bn == 128) return launch_pixel<64, 128>(P, veca, vecb, st);
-    return launch_pixel<64, 64>(P, veca, vecb, st);
+    switch (w.variant) {
+        case 0: return launch_pixel<128, 128, 16, 2, 2, 1>(P, veca, vecb, st);
+        case 1: return launch_pixel<128, 64, 32, 2, 1, 2>(P, veca, vecb, st);
+        case 2: return launch_pixel<64, 128, 32, 1, 2, 2>(P, veca, vecb, st);
+        case 3: return launch_pixel<64, 64, 32, 1, 1, 4>(P, veca, vecb, st);
+        case 4: return launch_pixel<64, 64, 16, 2, 2, 1>(P, veca, vecb, st);
+        case 5: return launch_pixel<128, 64, 16, 2, 2, 1>(P, veca, vecb, st);
+        default: return launch_pixel<64, 128, 16, 2, 2, 1>(P, veca, vecb, st);
+    }
 }
 
 int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream)

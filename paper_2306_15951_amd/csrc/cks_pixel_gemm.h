@@ -9,9 +9,13 @@
 // stored (no zero is ever inserted), X with a leaping step s.  One k is one
 // contiguous OC-row of dY and one contiguous IC-row of X.
 //
-// A workgroup owns (segment z of the pixel range, tap, BM oc, BN ic).  Segment
-// z of G_Z writes its partial result to slice z of the workspace; a second
-// kernel adds the slices in a fixed order.
+// The contraction axis is split at two levels:
+//   * between workgroups: segment z of G_Z writes its partial result to slice z
+//     of the workspace; a second kernel adds the slices in a fixed order;
+//   * inside a workgroup whose tile is smaller than 128x128: the WAVES_K waves
+//     that share a tile each take every WAVES_K-th part of a K-chunk, so that
+//     every wave still owns a 64x64 block of accumulators, and their results
+//     are added through LDS in a fixed tree before the store.
 #pragma once
 #include "cks_device.h"
 
@@ -26,8 +30,11 @@ struct PixelGemmParams {
     long sliceElems;  // OC*FH*FW*IC
 };
 
-// "advance a pixel counter by d" without division:  d = qn*(nOH*nOW) + rh*nOW + rw
+// Pixel counter inside a tap's trimmed range: k = (n*nOH + a)*nOW + b.
+struct Pix { int n, a, b; };
+// "advance by d" without division:  d = (qn*nOH + rh)*nOW + rw
 struct PixStep { int qn, rh, rw; };
+
 __device__ inline PixStep make_step(int d, int nOH, int nOW)
 {
     PixStep st;
@@ -37,18 +44,33 @@ __device__ inline PixStep make_step(int d, int nOH, int nOW)
     st.rh = q - st.qn * nOH;
     return st;
 }
+__device__ inline Pix advance(Pix x, PixStep st, int nOH, int nOW)
+{
+    x.b += st.rw;
+    int c = x.b >= nOW;
+    x.b -= c ? nOW : 0;
+    x.a += st.rh + c;
+    c = x.a >= nOH;
+    x.a -= c ? nOH : 0;
+    x.n += st.qn + c;
+    return x;
+}
 
-template <int BM, int BN>
-constexpr size_t pixel_lds_bytes() { return (size_t)2 * 16 * (BM + 32 + BN + 32) * sizeof(float); }
+template <int BM, int BN, int KC>
+constexpr size_t pixel_lds_bytes() { return (size_t)2 * KC * (BM + 32 + BN + 32) * sizeof(float); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VECA, bool VECB>
+template <int BM, int BN, int KC, int WAVES_M, int WAVES_N, int WAVES_K, bool VECA, bool VECB>
 __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
 {
-    constexpr int KC = 16;
     constexpr int LDA = BM + 32, LDB = BN + 32;   // +32: the two lane halves (k, k+1) hit disjoint banks
     constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
-    constexpr int PA = BM / 64, PB = BN / 64;
-    static_assert(WAVES_M * WAVES_N == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1, "tile shape");
+    constexpr int PA = BM / 64, PB = BN / 64;     // 16-byte loads per thread and pixel row
+    constexpr int PK = KC / 16;                   // pixel rows per thread and chunk
+    constexpr int KW = KC / WAVES_K;              // k handled by one wave per chunk
+    static_assert(WAVES_M * WAVES_N * WAVES_K == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1 && PK >= 1 &&
+                  KW % 2 == 0, "tile shape");
+    static_assert((size_t)(WAVES_K / 2) * WAVES_M * WAVES_N * TM * TN * 1024 * 4 <= pixel_lds_bytes<BM, BN, KC>(),
+                  "the wave reduction reuses the staging buffers");
 
     extern __shared__ __align__(16) float smem[];
     float *As = smem;                 // [2][KC][LDA]   dY rows
@@ -74,21 +96,25 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
     const int T = (kend - kbeg + KC - 1) / KC;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int wk = wave % WAVES_K, wn = (wave / WAVES_K) % WAVES_N, wm = wave / (WAVES_K * WAVES_N);
 
-    // Staging: thread (lr, lc) fetches pixel kbeg + t*KC + lr, 16 bytes at
-    // channel lc (+64, ...) of both operands.  (n, a, b) is that pixel's
-    // (image, row, column) inside the trimmed range, advanced by carries.
+    // Staging: thread (lr, lc) fetches pixel rows lr, lr+16, .. of a chunk, 16
+    // bytes at channel lc (+64, ...) of both operands.
     const int lr = tid >> 4, lc = (tid & 15) * 4;
-    int pn = 0, pa_ = 0, pb_ = 0;
+    Pix px[PK];
     PixStep stepKC = {0, 0, 0};
     if (T > 0) {
-        int k = kbeg + lr;
-        int q = k / nOW;
-        pb_ = k - q * nOW;
-        pn = q / nOH;
-        pa_ = q - pn * nOH;
+        const PixStep step16 = make_step(16, nOH, nOW);
         stepKC = make_step(KC, nOH, nOW);
+        const int k = kbeg + lr, q = k / nOW;
+        px[0].b = k - q * nOW;
+        px[0].n = q / nOH;
+        px[0].a = q - px[0].n * nOH;
+#pragma unroll
+        for (int r = 1; r < PK; ++r) px[r] = advance(px[r - 1], step16, nOH, nOW);
+    } else {
+#pragma unroll
+        for (int r = 0; r < PK; ++r) px[r] = Pix{0, 0, 0};
     }
     int kcur = kbeg + lr;
 
@@ -100,47 +126,43 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[PA], rb[PB];
-    auto gload = [&]() {
-        const bool live = kcur < kend;
-        const int oh = oh_s + pa_, ow = ow_s + pb_;
-        const float *ya = P.dY + (((long)pn * P.OH + oh) * P.OW + ow) * P.OC + m0 + lc;
-        const float *xb = P.X + (((long)pn * P.IH + (oh * P.s + ih_s)) * P.IW + (ow * P.s + iw_s)) * P.IC + n0 + lc;
+    // The loads of chunk t+1 are issued before chunk t is multiplied out of LDS
+    // and stored to the other LDS buffer after it.
+    struct Stage { float4 a[PK][PA], b[PK][PB]; };
+    Stage S0;
+    auto gload = [&](Stage &S) {
 #pragma unroll
-        for (int i = 0; i < PA; ++i) ra[i] = load4<VECA>(ya + 64 * i, live ? P.OC - (m0 + lc + 64 * i) : 0);
+        for (int r = 0; r < PK; ++r) {
+            const bool live = kcur + 16 * r < kend;   // dead rows (past the segment) read nothing: zeros
+            const int oh = oh_s + px[r].a, ow = ow_s + px[r].b;
+            const float *ya = P.dY + (((long)px[r].n * P.OH + oh) * P.OW + ow) * P.OC + m0 + lc;
+            const float *xb =
+                P.X + (((long)px[r].n * P.IH + (oh * P.s + ih_s)) * P.IW + (ow * P.s + iw_s)) * P.IC + n0 + lc;
 #pragma unroll
-        for (int i = 0; i < PB; ++i) rb[i] = load4<VECB>(xb + 64 * i, live ? P.IC - (n0 + lc + 64 * i) : 0);
-        // advance to the same row of the next chunk
+            for (int i = 0; i < PA; ++i) S.a[r][i] = load4<VECA>(ya + 64 * i, live ? P.OC - (m0 + lc + 64 * i) : 0);
+#pragma unroll
+            for (int i = 0; i < PB; ++i) S.b[r][i] = load4<VECB>(xb + 64 * i, live ? P.IC - (n0 + lc + 64 * i) : 0);
+            px[r] = advance(px[r], stepKC, nOH, nOW);   // same row of the next chunk
+        }
         kcur += KC;
-        pb_ += stepKC.rw;
-        int c = pb_ >= nOW;
-        pb_ -= c ? nOW : 0;
-        pa_ += stepKC.rh + c;
-        c = pa_ >= nOH;
-        pa_ -= c ? nOH : 0;
-        pn += stepKC.qn + c;
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](const Stage &S, int buf) {
 #pragma unroll
-        for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[(buf * KC + lr) * LDA + lc + 64 * i]) = ra[i];
+        for (int r = 0; r < PK; ++r) {
 #pragma unroll
-        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(&Bs[(buf * KC + lr) * LDB + lc + 64 * i]) = rb[i];
+            for (int i = 0; i < PA; ++i)
+                *reinterpret_cast<float4 *>(&As[(buf * KC + lr + 16 * r) * LDA + lc + 64 * i]) = S.a[r][i];
+#pragma unroll
+            for (int i = 0; i < PB; ++i)
+                *reinterpret_cast<float4 *>(&Bs[(buf * KC + lr + 16 * r) * LDB + lc + 64 * i]) = S.b[r][i];
+        }
     };
-
-    if (T > 0) {
-        gload();
-        sstore(0);
-    }
-    __syncthreads();
-    const int fcol = lane & 31, fk = lane >> 5;
-    for (int t = 0; t < T; ++t) {
-        const int buf = t & 1;
-        const bool more = t + 1 < T;
-        if (more) gload();
+    const int fcol = lane & 31, fk = wk * KW + (lane >> 5);
+    auto compute = [&](int buf) {
         const float *Ab = As + (buf * KC + fk) * LDA + wm * TM * 32 + fcol;
         const float *Bb = Bs + (buf * KC + fk) * LDB + wn * TN * 32 + fcol;
 #pragma unroll
-        for (int kk = 0; kk < KC / 2; ++kk) {
+        for (int kk = 0; kk < KW / 2; ++kk) {
             float a[TM], b[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) a[i] = Ab[kk * 2 * LDA + i * 32];
@@ -151,8 +173,55 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
         }
-        if (more) sstore(buf ^ 1);
+    };
+
+    gload(S0);          // chunk 0 (zeros when the segment is empty)
+    sstore(S0, 0);
+    __syncthreads();
+    for (int t = 0; t < T; ++t) {
+        gload(S0);      // chunk t+1; past the end of the segment every row is dead
+        compute(t & 1);
+        sstore(S0, (t + 1) & 1);
         __syncthreads();
+    }
+
+    // Add the WAVES_K partial tiles: in each round the upper half of the
+    // remaining waves hands its accumulators to the lower half through LDS.
+    if (WAVES_K > 1) {
+        float4 *red = reinterpret_cast<float4 *>(smem);
+#pragma unroll
+        for (int h = WAVES_K / 2; h >= 1; h /= 2) {
+            // slot of the (wm, wn, wk - h) tile: TM*TN*4 float4 per lane
+            if (wk >= h && wk < 2 * h) {
+                float4 *dst = red + (size_t)(((wm * WAVES_N + wn) * h + (wk - h)) * TM * TN * 4) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            dst[((i * TN + j) * 4 + q) * 64] = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
+                                                                           acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            }
+            __syncthreads();
+            if (wk < h) {
+                const float4 *src = red + (size_t)(((wm * WAVES_N + wn) * h + wk) * TM * TN * 4) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 v = src[((i * TN + j) * 4 + q) * 64];
+                            acc[i][j][4 * q] += v.x;
+                            acc[i][j][4 * q + 1] += v.y;
+                            acc[i][j][4 * q + 2] += v.z;
+                            acc[i][j][4 * q + 3] += v.w;
+                        }
+            }
+            __syncthreads();
+        }
+        if (wk != 0) return;
     }
 
     float *out = P.Out + (long)z * P.sliceElems;

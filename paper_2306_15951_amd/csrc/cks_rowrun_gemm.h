@@ -33,7 +33,16 @@ struct RowRunParams {
     float *Out;       // Y (fwd) or dX (deconv)
     int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
     int CHp, CWp;     // ceil(FH/s), ceil(FW/s): padded sub-kernel extents
-    int mTiles, nTiles, total, perXcd;
+    // Work decomposition: one output position (of Y, resp. dX) times one tile.
+    // Positions are issued roughly most expensive first: the list starts at
+    // (rotH, rotW), the first position with an untrimmed window, and wraps
+    // around to the border; KS-deconv in addition lists the positions class by
+    // class (larger sub-kernels first).
+    int itemsH, itemsW;   // grid of positions
+    int rotH, rotW;
+    int mTiles, nTiles;
+    int bandBlocks;       // workgroups per band = items per band * mTiles * nTiles
+    int total;            // workgroups with work
 };
 
 struct RunSet {
@@ -57,15 +66,15 @@ __device__ inline int class_major_index(int a, int I, int s, int p)
     return 0;  // not reached for 0 <= a < I
 }
 
+// Trim and addressing of one output position: (oh,ow) of Y for ConvV2, (ih,iw)
+// of dX for KS-deconv.
 template <int OP>
-__device__ inline RunSet decode_position(const RowRunParams &P, int pos)
+__device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 {
     RunSet R;
     if (OP == OP_FWD) {
         // Algorithm 1: trim [fh_s,fh_e) x [fw_s,fw_e) of the filter at (oh,ow).
-        // Interior positions (full filter, most work) are issued first.
-        int a = pos / P.OW, b = pos - a * P.OW;
-        int oh = (a + cdiv_any(P.p, P.s)) % P.OH, ow = (b + cdiv_any(P.p, P.s)) % P.OW;
+        const int oh = ph, ow = pw;
         int ih_s = oh * P.s - P.p, iw_s = ow * P.s - P.p;
         int fh_s = max(-ih_s, 0), fh_e = min(P.IH - ih_s, P.FH);
         int fw_s = max(-iw_s, 0), fw_e = min(P.IW - iw_s, P.FW);
@@ -83,8 +92,7 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int pos)
     } else {
         // Algorithm 2B: class (y,x) of (ih,iw), its sub-kernel extent CH x CW,
         // the window start (oh_s,ow_s) in dY and the trim [ch_s,ch_e) x [cw_s,cw_e).
-        int a = pos / P.IW, b = pos - a * P.IW;
-        int ih = class_major_index(a, P.IH, P.s, P.p), iw = class_major_index(b, P.IW, P.s, P.p);
+        const int ih = ph, iw = pw;
         int y = (ih + P.p) % P.s, x = (iw + P.p) % P.s;
         int CH = y < P.FH ? (P.FH - y + P.s - 1) / P.s : 0;
         int CW = x < P.FW ? (P.FW - x + P.s - 1) / P.s : 0;
@@ -107,6 +115,18 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int pos)
     return R;
 }
 
+// Hardware hands workgroup b to die b % 8.  Work is cut into bands of
+// bandBlocks consecutive workgroups (tiles of neighbouring items, which share
+// operands and so that die's L2); bands go to the dies in a serpentine order,
+// so every die gets the same mix of expensive interior and cheap border items.
+__device__ inline int banded_work(int bid, int bandBlocks)
+{
+    const int xcd = bid % kXcds, slot = bid / kXcds;
+    const int round = slot / bandBlocks;
+    const int band = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
+    return band * bandBlocks + slot % bandBlocks;
+}
+
 // Workgroup tile BM (batch rows) x BN (channels), K-chunk of 32 floats, LDS
 // double-buffered, rows padded to 36 floats so that the 16-byte fragment reads
 // of 32 consecutive rows spread over all banks.  4 waves as WAVES_M x WAVES_N,
@@ -126,12 +146,18 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     float *As = smem;                 // [2][BM][LDK]
     float *Bs = smem + 2 * BM * LDK;  // [2][BN][LDK]
 
-    const int work = xcd_contiguous_work(blockIdx.x, P.perXcd);
+    const int work = banded_work(blockIdx.x, P.bandBlocks);
     if (work >= P.total) return;
     const int nt = work % P.nTiles;
     const int mt = (work / P.nTiles) % P.mTiles;
-    const int pos = work / (P.nTiles * P.mTiles);
-    const RunSet R = decode_position<OP>(P, pos);
+    const int item = work / (P.nTiles * P.mTiles);
+    int ph = item / P.itemsW, pw = item % P.itemsW;
+    ph = (ph + P.rotH) % P.itemsH;
+    pw = (pw + P.rotW) % P.itemsW;
+    if (OP == OP_DECONV) {
+        ph = class_major_index(ph, P.IH, P.s, P.p);
+        pw = class_major_index(pw, P.IW, P.s, P.p);
+    }
     const int m0 = mt * BM, n0 = nt * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -139,6 +165,10 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 
     // Global -> LDS staging: 8 threads cover one 32-float row chunk (128 B).
     const int lr = tid >> 3, lc = (tid & 7) * 4;
+    const int frow = lane & 31, fk = (lane >> 5) * 4;
+
+    const RunSet R = decode_position<OP>(P, ph, pw);
+
     const float *pa[PA], *pb[PB];
 #pragma unroll
     for (int i = 0; i < PA; ++i) pa[i] = P.A + (long)min(m0 + lr + 32 * i, P.N - 1) * R.strideA + R.a0 + lc;
@@ -156,69 +186,63 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[PA], rb[PB];
-    auto gload = [&](int run, int ck) {
+    // One register set: the loads of chunk t+1 are issued before chunk t is
+    // multiplied out of LDS and stored to the other LDS buffer after it.  (A
+    // second set, two chunks ahead, was measured to be slower.)
+    // `live` false: nothing is read and zeros are staged.
+    struct Stage { float4 a[PA], b[PB]; };
+    Stage S0;
+    auto gload = [&](Stage &S, int run, int ck, bool live) {
         const long oa = run * R.aRun + ck * KC, ob = run * R.bRun + ck * KC;
-        const int valid = R.L - ck * KC - lc;
+        const int valid = live ? R.L - ck * KC - lc : 0;
 #pragma unroll
-        for (int i = 0; i < PA; ++i) ra[i] = load4<VEC>(pa[i] + oa, valid);
+        for (int i = 0; i < PA; ++i) S.a[i] = load4<VEC>(pa[i] + oa, valid);
 #pragma unroll
-        for (int i = 0; i < PB; ++i) rb[i] = load4<VEC>(pb[i] + ob, valid);
+        for (int i = 0; i < PB; ++i) S.b[i] = load4<VEC>(pb[i] + ob, valid);
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](const Stage &S, int buf) {
 #pragma unroll
-        for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[(buf * BM + lr + 32 * i) * LDK + lc]) = ra[i];
+        for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[(buf * BM + lr + 32 * i) * LDK + lc]) = S.a[i];
 #pragma unroll
-        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(&Bs[(buf * BN + lr + 32 * i) * LDK + lc]) = rb[i];
+        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(&Bs[(buf * BN + lr + 32 * i) * LDK + lc]) = S.b[i];
     };
 
     // MFMA fragments: lane l reads 4 consecutive k of row (l%32); the two lane
-    // halves take k-groups 4 apart, so one 16-byte read feeds 4 MFMAs.
-    const int frow = lane & 31, fk = (lane >> 5) * 4;
-    auto kstep = [&](const float *Ab, const float *Bb, int kk) {
-        float4 a[TM], b[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4 *>(Ab + i * 32 * LDK + kk * 8);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4 *>(Bb + j * 32 * LDK + kk * 8);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                acc[i][j] = mfma32(a[i].x, b[j].x, acc[i][j]);
-                acc[i][j] = mfma32(a[i].y, b[j].y, acc[i][j]);
-                acc[i][j] = mfma32(a[i].z, b[j].z, acc[i][j]);
-                acc[i][j] = mfma32(a[i].w, b[j].w, acc[i][j]);
-            }
-    };
-
-    int run = 0, ck = 0;
-    if (T > 0) {
-        gload(0, 0);
-        sstore(0);
-    }
-    __syncthreads();
-    for (int t = 0; t < T; ++t) {
-        const int buf = t & 1;
-        int nrun = run, nck = ck + 1;
-        if (nck == cpr) { nck = 0; ++nrun; }
-        const bool more = t + 1 < T;
-        if (more) gload(nrun, nck);
-
+    // halves take k-groups 4 apart, so one 16-byte read feeds 4 MFMAs.  A chunk
+    // shorter than 32 is zero-filled in LDS, so every chunk runs the same 4 steps
+    // and the accumulators never leave their registers.
+    auto compute = [&](int buf) {
         const float *Ab = As + (buf * BM + wm * TM * 32 + frow) * LDK + fk;
         const float *Bb = Bs + (buf * BN + wn * TN * 32 + frow) * LDK + fk;
-        const int nk = (min(KC, R.L - ck * KC) + 7) >> 3;
-        if (nk == KC / 8) {
 #pragma unroll
-            for (int kk = 0; kk < KC / 8; ++kk) kstep(Ab, Bb, kk);
-        } else {
-            for (int kk = 0; kk < nk; ++kk) kstep(Ab, Bb, kk);
+        for (int kk = 0; kk < KC / 8; ++kk) {
+            float4 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4 *>(Ab + i * 32 * LDK + kk * 8);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4 *>(Bb + j * 32 * LDK + kk * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = mfma32(reinterpret_cast<const float *>(&a[i])[e],
+                                           reinterpret_cast<const float *>(&b[j])[e], acc[i][j]);
         }
+    };
 
-        if (more) sstore(buf ^ 1);
+    int run = 0, ck = 0;   // chunk being loaded
+    auto next_chunk = [&]() { if (++ck == cpr) { ck = 0; ++run; } };
+    gload(S0, 0, 0, T > 0);
+    sstore(S0, 0);
+    __syncthreads();
+    for (int t = 0; t < T; ++t) {
+        next_chunk();
+        gload(S0, run, ck, t + 1 < T);
+        compute(t & 1);
+        sstore(S0, (t + 1) & 1);
         __syncthreads();
-        run = nrun;
-        ck = nck;
     }
 
     // Every output element of the tile is stored, also when the trimmed range
