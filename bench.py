@@ -97,6 +97,21 @@ class LayerBench:
         return e0.elapsed_time(e1) / iters
 
 
+def measured_traffic(workload, kernel_prefix):
+    """HBM bytes per launch of a kernel, from the committed rocprofv3 counter
+    summary of this workload (profiles/bench_<workload>_traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        f = line.rstrip("\n").split("\t")
+        if len(f) == 3 and f[0].startswith(kernel_prefix):
+            return float(f[1]) + float(f[2])
+    return None
+
+
 def cpu_baseline(L, host, useful_flops, budget_s=6.0):
     """The oracle as it stands, on a random sample of outputs of each operator,
     sized from a short calibration so that each operator takes about budget_s."""
@@ -172,6 +187,8 @@ def main():
     mains = {k: r["kernel_ms"][k] for k in ("rowrun_gemm<fwd>", "rowrun_gemm<deconv>", "pixel_gemm")}
     dom = max(mains, key=mains.get)
     achieved = B.useful_flops / mains[dom] / 1e9
+    prefix = {"rowrun_gemm<fwd>": "cks::rowrun_gemm<0", "rowrun_gemm<deconv>": "cks::rowrun_gemm<1",
+              "pixel_gemm": "cks::pixel_gemm"}[dom]
     line = {
         "metric": METRIC, "value": r["step_tflops"], "unit": "TFLOP/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": r["ms_per_step"],
@@ -181,7 +198,8 @@ def main():
         "pct_fp32_mfma_peak": 100 * r["step_tflops"] / PEAK_FP32_MFMA_TFLOPS,
         "operators": r["operators"], "kernel_ms": r["kernel_ms"],
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": measured_traffic(a.config, prefix), "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE)",
                      "all_main_kernels": {k: B.useful_flops / v / 1e9 for k, v in mains.items()}},
     }
     if not a.no_cpu_baseline:
