@@ -8,6 +8,7 @@
 #include <cstdlib>
 
 #include "cks_pack.h"
+#include "cks_patch_gemm.h"
 #include "cks_pixel_gemm.h"
 #include "cks_rowrun_gemm.h"
 
@@ -145,6 +146,7 @@ int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int 
 // ---------------------------------------------------------------- Sk-dilated
 
 struct WgradPlan {
+    int patch;    // 0: one tile per filter tap (pixel_gemm); 1..3: all taps in one tile (patch_gemm), see below
     int variant, bm, bn, mTiles, nTiles, GZ;
 };
 
@@ -165,11 +167,38 @@ constexpr int kWgradVariants[][6] = {
 WgradPlan plan_wgrad(const Geo &g)
 {
     WgradPlan w;
+    w.patch = 0;
+    const char *tune = getenv("CKS_TUNE_WGRAD");   // "variant[,G_Z]": tuning experiments only
+    // Few input channels: a per-tap tile would be narrower than an MFMA block.
+    // Put the whole filter patch (J = FH*FW*IC columns) into one tile if it
+    // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
+    const long long J = (long long)g.FH * g.FW * g.C;
+    if (g.C < 96 && J <= 576 && !(tune && tune[0] == 't')) {
+        const int nb = J <= 160 ? 5 : (J <= 320 ? 10 : 18);
+        if (10 * J >= 7 * 32 * nb) {
+            w.patch = nb == 5 ? 1 : (nb == 10 ? 2 : 3);
+            w.variant = -1;
+            w.bm = 64; w.bn = 32 * nb;
+            w.mTiles = (g.OC + 63) / 64; w.nTiles = 1;
+            const long long K = (long long)g.N * g.OH * g.OW;
+            // workgroups per compute unit that fit its LDS: one for the 18-block tile, else two
+            long long gz = ((w.patch == 3 ? 1LL : 2LL) * kCUs + w.mTiles - 1) / w.mTiles;
+            gz = gz < K / 256 ? gz : K / 256;
+            if (tune && tune[0] == 'p') {
+                const int z = atoi(tune + 1);
+                if (z > 0) gz = z;
+            }
+            if (gz < 1) gz = 1;
+            w.GZ = (int)gz;
+            return w;
+        }
+    }
     const bool bigM = g.OC >= 96, bigN = g.C >= 96;
     w.variant = bigM && bigN ? 0 : (bigM ? 5 : (bigN ? 6 : 4));
     long long gz_override = 0;
-    if (const char *t = getenv("CKS_TUNE_WGRAD")) {   // "variant[,G_Z]" -- for tuning experiments
+    if (const char *t = tune) {
         int v = -1, z = 0;
+        if (t[0] == 't') ++t;
         if (sscanf(t, "%d,%d", &v, &z) >= 1 && v >= 0 && v < 7) w.variant = v;
         gz_override = z;
     }
@@ -197,6 +226,17 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
     if (veca) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
     if (vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, true>, P, blocks, lds, st);
     return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, false>, P, blocks, lds, st);
+}
+
+template <int WM, int WN, int WK, int NBW, int KC>
+int launch_patch(PatchGemmParams P, bool veca, bool vecb, hipStream_t st)
+{
+    const size_t lds = patch_lds_bytes<WM, WN, NBW, KC>();
+    const int blocks = P.perXcd * kXcds;
+    if (veca && vecb) return launch(patch_gemm<WM, WN, WK, NBW, KC, true, true>, P, blocks, lds, st);
+    if (veca) return launch(patch_gemm<WM, WN, WK, NBW, KC, true, false>, P, blocks, lds, st);
+    if (vecb) return launch(patch_gemm<WM, WN, WK, NBW, KC, false, true>, P, blocks, lds, st);
+    return launch(patch_gemm<WM, WN, WK, NBW, KC, false, false>, P, blocks, lds, st);
 }
 
 }  // namespace
@@ -329,6 +369,24 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
     if (rc != CKS_OK) return rc;
     if (!X || !dY || !part) return CKS_ERR_NULL;
     const WgradPlan w = plan_wgrad(g);
+    const bool veca = (OC % 4 == 0) && aligned16(dY);
+    const bool vecb = (C % 4 == 0) && aligned16(X);
+    hipStream_t st = (hipStream_t)stream;
+    if (w.patch) {
+        PatchGemmParams Q{};
+        Q.X = X; Q.dY = dY; Q.Out = part;
+        Q.N = N; Q.IC = C; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW;
+        Q.FH = FH; Q.FW = FW; Q.s = stride; Q.p = padding;
+        Q.GZ = w.GZ; Q.mTiles = w.mTiles;
+        Q.total = w.GZ * w.mTiles;
+        Q.perXcd = (Q.total + kXcds - 1) / kXcds;
+        Q.sliceElems = (long)OC * FH * FW * C;
+        switch (w.patch) {
+            case 1: return launch_patch<2, 1, 2, 5, 32>(Q, veca, vecb, st);
+            case 2: return launch_patch<2, 2, 1, 5, 16>(Q, veca, vecb, st);
+            default: return launch_patch<2, 2, 1, 9, 16>(Q, veca, vecb, st);
+        }
+    }
     const long long total = (long long)w.GZ * FH * FW * w.mTiles * w.nTiles;
     if (!fits_i31(total + kXcds)) return CKS_ERR_SHAPE;
 
@@ -340,9 +398,6 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
     P.total = (int)total;
     P.perXcd = (P.total + kXcds - 1) / kXcds;
     P.sliceElems = (long)OC * FH * FW * C;
-    const bool veca = (OC % 4 == 0) && aligned16(dY);
-    const bool vecb = (C % 4 == 0) && aligned16(X);
-    hipStream_t st = (hipStream_t)stream;
     switch (w.variant) {
         case 0: return launch_pixel<128, 128, 16, 2, 2, 1>(P, veca, vecb, st);
         case 1: return launch_pixel<128, 64, 32, 2, 1, 2>(P, veca, vecb, st);
@@ -358,8 +413,15 @@ int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segment
 {
     if (elems <= 0 || segments < 1 || !fits_i31(elems)) return CKS_ERR_SHAPE;
     if (!part || !dW) return CKS_ERR_NULL;
-    hipLaunchKernelGGL(reduce_slices, dim3((unsigned)((elems + kThreads - 1) / kThreads)), dim3(kThreads), 0,
-                       (hipStream_t)stream, part, dW, (long)elems, segments);
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec = elems % 4 == 0 && aligned16(part) && aligned16(dW);
+    const int zl = segments >= 32 ? 16 : 1;                 // z-lanes per element
+    const long per_block = (long)(kThreads / zl) * (vec ? 4 : 1);
+    const dim3 grid((unsigned)((elems + per_block - 1) / per_block)), block(kThreads);
+    if (zl == 16 && vec) hipLaunchKernelGGL((reduce_slices<16, 4>), grid, block, 0, st, part, dW, (long)elems, segments);
+    else if (zl == 16) hipLaunchKernelGGL((reduce_slices<16, 1>), grid, block, 0, st, part, dW, (long)elems, segments);
+    else if (vec) hipLaunchKernelGGL((reduce_slices<1, 4>), grid, block, 0, st, part, dW, (long)elems, segments);
+    else hipLaunchKernelGGL((reduce_slices<1, 1>), grid, block, 0, st, part, dW, (long)elems, segments);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? CKS_OK : hip_fail(e);
 }

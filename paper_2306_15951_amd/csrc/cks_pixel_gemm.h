@@ -238,14 +238,48 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
         }
 }
 
-// dW[e] = sum_z part[z][e], z ascending: a fixed order, so two runs agree bit for bit.
+// dW[e] = sum_z part[z][e] in a fixed association, so two runs agree bit for
+// bit: z-lane l of ZL adds slices l, l+ZL, l+2ZL, ... in ascending order, then
+// the ZL lane sums are added in ascending lane order.  A workgroup covers
+// (256/ZL)*VW consecutive elements; VW = 4 uses 16-byte accesses.
+template <int ZL, int VW>
 __global__ void __launch_bounds__(kThreads) reduce_slices(const float *part, float *dW, long elems, int GZ)
 {
-    const long e = (long)blockIdx.x * kThreads + threadIdx.x;
-    if (e >= elems) return;
-    float s = 0.f;
-    for (int z = 0; z < GZ; ++z) s += part[(long)z * elems + e];
-    dW[e] = s;
+    constexpr int COLS = kThreads / ZL;
+    __shared__ float red[ZL > 1 ? kThreads * VW : 1];
+    const int col = threadIdx.x % COLS, zl = threadIdx.x / COLS;
+    const long e = ((long)blockIdx.x * COLS + col) * VW;
+    float s[VW];
+#pragma unroll
+    for (int v = 0; v < VW; ++v) s[v] = 0.f;
+    if (e < elems) {
+        const float *p = part + e + (long)zl * elems;
+        const long step = (long)ZL * elems;
+        for (int z = zl; z < GZ; z += ZL, p += step) {
+            if (VW == 4) {
+                const float4 t = *reinterpret_cast<const float4 *>(p);
+                s[0] += t.x; s[VW > 1 ? 1 : 0] += t.y; s[VW > 2 ? 2 : 0] += t.z; s[VW > 3 ? 3 : 0] += t.w;
+            } else {
+                s[0] += p[0];
+            }
+        }
+    }
+    if (ZL > 1) {
+#pragma unroll
+        for (int v = 0; v < VW; ++v) red[(zl * VW + v) * COLS + col] = s[v];
+        __syncthreads();
+        if (zl != 0 || e >= elems) return;
+#pragma unroll
+        for (int v = 0; v < VW; ++v) {
+            float t = red[v * COLS + col];
+            for (int l = 1; l < ZL; ++l) t += red[(l * VW + v) * COLS + col];
+            s[v] = t;
+        }
+    } else if (e >= elems) {
+        return;
+    }
+    if (VW == 4) *reinterpret_cast<float4 *>(dW + e) = make_float4(s[0], s[VW > 1 ? 1 : 0], s[VW > 2 ? 2 : 0], s[VW > 3 ? 3 : 0]);
+    else dW[e] = s[0];
 }
 
 }  // namespace cks

@@ -125,6 +125,12 @@ MID = [
     ("single_image", 1, 16, 12, 12, 16, 3, 3, 1, 1),
     ("filter_covers_map", 8, 4, 3, 3, 4, 5, 5, 1, 2),
     ("small_map_big_batch", 300, 20, 4, 4, 24, 3, 3, 1, 1),
+    # few input channels: the filter gradient puts the whole filter patch in one tile
+    ("patch_ic16", 40, 16, 9, 10, 70, 3, 3, 1, 1),
+    ("patch_ic32_s2", 24, 32, 11, 9, 40, 3, 3, 2, 1),
+    ("patch_ic5_5x5", 12, 5, 12, 13, 33, 5, 5, 2, 2),
+    ("patch_ic60", 16, 60, 8, 8, 64, 3, 3, 1, 1),
+    ("patch_ic3_pad_ge_filter", 6, 3, 6, 7, 8, 7, 7, 3, 7),
 ]
 
 
