@@ -8,6 +8,7 @@
 #include <cstdlib>
 
 #include "cks_pack.h"
+#include "cks_patch_fwd.h"
 #include "cks_patch_gemm.h"
 #include "cks_pixel_gemm.h"
 #include "cks_rowrun_gemm.h"
@@ -47,14 +48,14 @@ inline int hip_fail(hipError_t e)
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 template <typename K, typename P>
-int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st)
+int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st, int threads = kThreads)
 {
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return hip_fail(e);
     }
-    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), lds, st, params);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), lds, st, params);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? CKS_OK : hip_fail(e);
 }
@@ -78,8 +79,17 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     P.total = (int)total;
     P.bandBlocks = (int)bandBlocks;
     const size_t lds = rowrun_lds_bytes<BM, BN>();
-    if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, true>, P, (int)blocks, lds, st);
-    return launch(rowrun_gemm<OP, BM, BN, WM, WN, false>, P, (int)blocks, lds, st);
+    // Fast loads need: 16-byte vectors, every run a whole number of 32-float
+    // chunks (the run is a multiple of the contracted channel count), and the
+    // tile's rows within 2 GiB of its first one.
+    const long long kch = OP == OP_FWD ? P.IC : P.OC;
+    const long long rowA = OP == OP_FWD ? (long long)P.IH * P.IW * P.IC : (long long)P.OH * P.OW * P.OC;
+    const long long rowB = OP == OP_FWD ? (long long)P.FH * P.FW * P.IC : (long long)P.CHp * P.CWp * P.OC;
+    const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (rowB * BN + rowB) * 4 < (1LL << 31) &&
+                      !getenv("CKS_TUNE_NO_FAST_LOADS");
+    if (fast) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
+    if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
+    return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_SCALAR>, P, (int)blocks, lds, st);
 }
 
 template <int OP>
@@ -312,6 +322,23 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
     int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
     if (rc != CKS_OK) return rc;
     if (!X || !Wt || !Y) return CKS_ERR_NULL;
+    // Image stems (very few input channels): one GEMM over all pixels with the
+    // whole filter patch as contraction axis and the filter resident in LDS.
+    const int KP = (FH * FW * C + 15) / 16 * 16;
+    if (C < 8 && KP <= kPatchFwdMaxKP && (long long)H * W * C * (18 / ((long long)g.OH * g.OW) + 2) < (1LL << 29) && !getenv("CKS_TUNE_NO_PATCH_FWD")) {
+        PatchFwdParams Q{};
+        Q.X = X; Q.W = Wt; Q.Y = Y;
+        Q.N = N; Q.IC = C; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW;
+        Q.FH = FH; Q.FW = FW; Q.s = stride; Q.p = padding;
+        Q.KP = KP;
+        Q.nT = (OC + 63) / 64;
+        Q.mTiles = (int)(((long long)N * g.OH * g.OW + 63) / 64);
+        const int groups = Q.mTiles < kCUs ? Q.mTiles : kCUs;    // one workgroup per compute unit (LDS)
+        Q.tilesPerBlock = (Q.mTiles + groups - 1) / groups;
+        const long long blocks = (long long)((Q.mTiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
+        if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
+        return launch(patch_fwd, Q, (int)blocks, patch_fwd_lds_bytes(KP), (hipStream_t)stream, kPatchFwdThreads);
+    }
     const bool vec = (C % 4 == 0) && aligned16(X) && aligned16(Wt);
     return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), N, OC, vec, (hipStream_t)stream);
 }

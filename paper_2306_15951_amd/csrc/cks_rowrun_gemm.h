@@ -134,9 +134,20 @@ __device__ inline int banded_work(int bid, int bandBlocks)
 template <int BM, int BN>
 constexpr size_t rowrun_lds_bytes() { return (size_t)2 * (BM + BN) * 36 * sizeof(float); }
 
-template <int OP, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC>
+// LOAD selects how the K-chunks are fetched:
+//   LOAD_SCALAR  4-byte loads, every element masked (any channel count, any alignment)
+//   LOAD_VEC     16-byte loads, masked per 4 floats (channel count multiple of 4, 16-byte aligned)
+//   LOAD_FAST    16-byte buffer loads with one scalar offset per chunk: the per-lane
+//                offsets are computed once, the run length is a multiple of 32 (no
+//                partial chunk, nothing to mask), so the loop issues no vector ALU
+//                instruction for addressing.  VALU instructions and MFMAs of one SIMD
+//                do not overlap, so every one removed from the loop is MFMA time won.
+enum { LOAD_SCALAR = 0, LOAD_VEC = 1, LOAD_FAST = 2 };
+
+template <int OP, int BM, int BN, int WAVES_M, int WAVES_N, int LOAD>
 __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 {
+    constexpr bool VEC = LOAD != LOAD_SCALAR;
     constexpr int KC = 32, LDK = KC + 4;
     constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
     constexpr int PA = BM / 32, PB = BN / 32;
@@ -169,12 +180,6 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 
     const RunSet R = decode_position<OP>(P, ph, pw);
 
-    const float *pa[PA], *pb[PB];
-#pragma unroll
-    for (int i = 0; i < PA; ++i) pa[i] = P.A + (long)min(m0 + lr + 32 * i, P.N - 1) * R.strideA + R.a0 + lc;
-#pragma unroll
-    for (int i = 0; i < PB; ++i) pb[i] = P.B + (long)min(n0 + lr + 32 * i, R.NC - 1) * R.strideB + R.b0 + lc;
-
     const int cpr = (R.L + KC - 1) / KC;  // chunks per run
     const int T = R.nruns * cpr;
 
@@ -186,41 +191,75 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // Row addresses of this thread's staging loads.  Rows past the end of the
+    // batch / channel range are clamped (loaded twice, never stored).
+    const float *pa[PA], *pb[PB];
+    unsigned va[PA], vb[PB];   // LOAD_FAST: byte offsets from the workgroup's base
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+        const int r = min(m0 + lr + 32 * i, P.N - 1);
+        pa[i] = P.A + (long)r * R.strideA + R.a0 + lc;
+        va[i] = (unsigned)(((long)(r - m0) * R.strideA + lc) * 4);
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+        const int c = min(n0 + lr + 32 * i, R.NC - 1);
+        pb[i] = P.B + (long)c * R.strideB + R.b0 + lc;
+        vb[i] = (unsigned)(((long)(c - n0) * R.strideB + lc) * 4);
+    }
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(P.A + (long)min(m0, P.N - 1) * R.strideA + R.a0), 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(P.B + (long)min(n0, R.NC - 1) * R.strideB + R.b0), 0, -1, 0x00020000);
+
     // One register set: the loads of chunk t+1 are issued before chunk t is
     // multiplied out of LDS and stored to the other LDS buffer after it.  (A
     // second set, two chunks ahead, was measured to be slower.)
-    // `live` false: nothing is read and zeros are staged.
     struct Stage { float4 a[PA], b[PB]; };
     Stage S0;
+    // `live` false: nothing is read; the masked modes then stage zeros.
     auto gload = [&](Stage &S, int run, int ck, bool live) {
-        const long oa = run * R.aRun + ck * KC, ob = run * R.bRun + ck * KC;
-        const int valid = live ? R.L - ck * KC - lc : 0;
+        if (LOAD == LOAD_FAST) {
+            if (!live) return;   // uniform
+            const int sa = (int)((run * R.aRun + ck * KC) * 4), sb = (int)((run * R.bRun + ck * KC) * 4);
 #pragma unroll
-        for (int i = 0; i < PA; ++i) S.a[i] = load4<VEC>(pa[i] + oa, valid);
+            for (int i = 0; i < PA; ++i)
+                S.a[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsA, va[i], sa, 0));
 #pragma unroll
-        for (int i = 0; i < PB; ++i) S.b[i] = load4<VEC>(pb[i] + ob, valid);
+            for (int i = 0; i < PB; ++i)
+                S.b[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsB, vb[i], sb, 0));
+        } else {
+            const long oa = run * R.aRun + ck * KC, ob = run * R.bRun + ck * KC;
+            const int valid = live ? R.L - ck * KC - lc : 0;
+#pragma unroll
+            for (int i = 0; i < PA; ++i) S.a[i] = load4<VEC>(pa[i] + oa, valid);
+#pragma unroll
+            for (int i = 0; i < PB; ++i) S.b[i] = load4<VEC>(pb[i] + ob, valid);
+        }
     };
+    // buf is a compile-time constant in the loop below, so every LDS access is
+    // "thread base + immediate"
+    float *const Aw = As + lr * LDK + lc, *const Bw = Bs + lr * LDK + lc;
     auto sstore = [&](const Stage &S, int buf) {
 #pragma unroll
-        for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[(buf * BM + lr + 32 * i) * LDK + lc]) = S.a[i];
+        for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(Aw + (buf * BM + 32 * i) * LDK) = S.a[i];
 #pragma unroll
-        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(&Bs[(buf * BN + lr + 32 * i) * LDK + lc]) = S.b[i];
+        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(Bw + (buf * BN + 32 * i) * LDK) = S.b[i];
     };
 
     // MFMA fragments: lane l reads 4 consecutive k of row (l%32); the two lane
     // halves take k-groups 4 apart, so one 16-byte read feeds 4 MFMAs.  A chunk
     // shorter than 32 is zero-filled in LDS, so every chunk runs the same 4 steps
     // and the accumulators never leave their registers.
+    const float *const Ar = As + (wm * TM * 32 + frow) * LDK + fk, *const Br = Bs + (wn * TN * 32 + frow) * LDK + fk;
     auto compute = [&](int buf) {
-        const float *Ab = As + (buf * BM + wm * TM * 32 + frow) * LDK + fk;
-        const float *Bb = Bs + (buf * BN + wn * TN * 32 + frow) * LDK + fk;
 #pragma unroll
         for (int kk = 0; kk < KC / 8; ++kk) {
             float4 a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4 *>(Ab + i * 32 * LDK + kk * 8);
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4 *>(Ar + (buf * BM + i * 32) * LDK + kk * 8);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4 *>(Bb + j * 32 * LDK + kk * 8);
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4 *>(Br + (buf * BN + j * 32) * LDK + kk * 8);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -234,15 +273,27 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 
     int run = 0, ck = 0;   // chunk being loaded
     auto next_chunk = [&]() { if (++ck == cpr) { ck = 0; ++run; } };
+    // The loop body handles two chunks with literal buffer numbers (all LDS
+    // addresses become immediates) and no branch around the MFMAs (so the
+    // accumulators stay in place).  An odd chunk count is peeled off in front:
+    // chunk 0 then starts in buffer 1.
+    const int odd = T & 1;
     gload(S0, 0, 0, T > 0);
-    sstore(S0, 0);
+    if (LOAD != LOAD_FAST || T > 0) {
+        if (odd) sstore(S0, 1); else sstore(S0, 0);
+    }
     __syncthreads();
-    for (int t = 0; t < T; ++t) {
+    auto iteration = [&](int t, int buf) {   // buf is a literal at every call
         next_chunk();
         gload(S0, run, ck, t + 1 < T);
-        compute(t & 1);
-        sstore(S0, (t + 1) & 1);
+        compute(buf);
+        if (LOAD != LOAD_FAST || t + 1 < T) sstore(S0, buf ^ 1);
         __syncthreads();
+    };
+    if (odd) iteration(0, 1);
+    for (int t = odd; t < T; t += 2) {
+        iteration(t, 0);
+        iteration(t + 1, 1);
     }
 
     // Every output element of the tile is stored, also when the trimmed range

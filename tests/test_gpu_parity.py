@@ -131,6 +131,8 @@ MID = [
     ("patch_ic5_5x5", 12, 5, 12, 13, 33, 5, 5, 2, 2),
     ("patch_ic60", 16, 60, 8, 8, 64, 3, 3, 1, 1),
     ("patch_ic3_pad_ge_filter", 6, 3, 6, 7, 8, 7, 7, 3, 7),
+    ("gray_1ch", 5, 1, 10, 11, 70, 3, 3, 1, 1),
+    ("ic7_5x5", 3, 7, 9, 9, 65, 5, 5, 1, 2),
 ]
 
 
