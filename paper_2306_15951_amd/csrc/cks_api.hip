@@ -171,9 +171,8 @@ constexpr int kWgradVariants[][6] = {
     {64, 128, 16, 2, 2, 1},   // 6
 };
 
-// G_Z: enough segments that the grid has about `target` workgroups, but never
-// segments shorter than 256 pixels (Section IV.C: the number of segments trades
-// parallelism against the memory for partial sums).
+// G_Z (Section IV.C: the number of segments trades parallelism against the
+// memory for partial sums) is derived from the compute-unit count, see below.
 WgradPlan plan_wgrad(const Geo &g)
 {
     WgradPlan w;
@@ -183,7 +182,7 @@ WgradPlan plan_wgrad(const Geo &g)
     // Put the whole filter patch (J = FH*FW*IC columns) into one tile if it
     // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
     const long long J = (long long)g.FH * g.FW * g.C;
-    if (g.C < 96 && J <= 576 && !(tune && tune[0] == 't')) {
+    if (g.C < 48 && J <= 576 && !(tune && tune[0] == 't')) {
         const int nb = J <= 160 ? 5 : (J <= 320 ? 10 : 18);
         if (10 * J >= 7 * 32 * nb) {
             w.patch = nb == 5 ? 1 : (nb == 10 ? 2 : 3);
@@ -218,8 +217,15 @@ WgradPlan plan_wgrad(const Geo &g)
     w.nTiles = (g.C + w.bn - 1) / w.bn;
     const long long tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
     const long long K = (long long)g.N * g.OH * g.OW;
-    long long gz = (4LL * kCUs + tiles - 1) / tiles;
+    // About four workgroups per compute unit, segments of at least 256 pixels,
+    // and -- since workgroups are dealt to the 8 dies in contiguous ranges of
+    // segments -- a multiple of 8 segments, so that every die works on whole
+    // segments (measured: 8 segments beat 7 or 9 by 10-15 %).
+    long long gz = 4LL * kCUs / tiles;
     gz = gz < K / 256 ? gz : K / 256;
+    if (gz >= kXcds) gz = gz / kXcds * kXcds;
+    else if (K / 256 >= kXcds && tiles * kXcds <= 8LL * kCUs) gz = kXcds;
+    if (gz < 1) gz = 1;
     if (gz_override > 0) gz = gz_override;
     if (gz < 1) gz = 1;
     if (gz > 512) gz = 512;
@@ -232,6 +238,10 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
 {
     const size_t lds = pixel_lds_bytes<BM, BN, KC>();
     const int blocks = P.perXcd * kXcds;
+    // batch-inner ordering with scalar chunk offsets (see pixel_gemm_fast)
+    const bool fast = veca && vecb && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
+                      (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS");
+    if (fast) return launch(pixel_gemm_fast<BM, BN, KC, WM, WN, WK>, P, blocks, lds, st);
     if (veca && vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
     if (veca) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
     if (vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, true>, P, blocks, lds, st);
@@ -243,6 +253,11 @@ int launch_patch(PatchGemmParams P, bool veca, bool vecb, hipStream_t st)
 {
     const size_t lds = patch_lds_bytes<WM, WN, NBW, KC>();
     const int blocks = P.perXcd * kXcds;
+    // batch-inner ordering with scalar chunk offsets (see patch_gemm_fast)
+    const bool fast = veca && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
+                      (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS");
+    // (with 4-byte items, i.e. IC not a multiple of 4, the pixel order coalesces better: neighbouring patches overlap)
+    if (fast && vecb) return launch(patch_gemm_fast<WM, WN, WK, NBW, KC, true>, P, blocks, lds, st);
     if (veca && vecb) return launch(patch_gemm<WM, WN, WK, NBW, KC, true, true>, P, blocks, lds, st);
     if (veca) return launch(patch_gemm<WM, WN, WK, NBW, KC, true, false>, P, blocks, lds, st);
     if (vecb) return launch(patch_gemm<WM, WN, WK, NBW, KC, false, true>, P, blocks, lds, st);

@@ -56,6 +56,63 @@ __device__ inline Pix advance(Pix x, PixStep st, int nOH, int nOW)
     return x;
 }
 
+// Shared tail of the filter-gradient kernels: add the WAVES_K partial tiles (in
+// each round the upper half of the remaining waves hands its accumulators to
+// the lower half through LDS: a fixed tree) and store the tile to slice z.
+template <int TM, int TN, int WAVES_M, int WAVES_N, int WAVES_K>
+__device__ inline void wgrad_tile_epilogue(floatx16 (&acc)[TM][TN], float *smem, const PixelGemmParams &P, int z, int tap,
+                                           int m0, int n0, int wm, int wn, int wk, int lane)
+{
+    if (WAVES_K > 1) {
+        float4 *red = reinterpret_cast<float4 *>(smem);
+#pragma unroll
+        for (int h = WAVES_K / 2; h >= 1; h /= 2) {
+            // slot of the (wm, wn, wk - h) tile: TM*TN*4 float4 per lane
+            if (wk >= h && wk < 2 * h) {
+                float4 *dst = red + (size_t)(((wm * WAVES_N + wn) * h + (wk - h)) * TM * TN * 4) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            dst[((i * TN + j) * 4 + q) * 64] = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
+                                                                           acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            }
+            __syncthreads();
+            if (wk < h) {
+                const float4 *src = red + (size_t)(((wm * WAVES_N + wn) * h + wk) * TM * TN * 4) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 v = src[((i * TN + j) * 4 + q) * 64];
+                            acc[i][j][4 * q] += v.x;
+                            acc[i][j][4 * q + 1] += v.y;
+                            acc[i][j][4 * q + 2] += v.z;
+                            acc[i][j][4 * q + 3] += v.w;
+                        }
+            }
+            __syncthreads();
+        }
+        if (wk != 0) return;
+    }
+    float *out = P.Out + (long)z * P.sliceElems;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int ic = n0 + (wn * TN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int oc = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (oc < P.OC && ic < P.IC) out[((long)oc * P.FH * P.FW + tap) * P.IC + ic] = acc[i][j][r];
+            }
+        }
+}
+
 template <int BM, int BN, int KC>
 constexpr size_t pixel_lds_bytes() { return (size_t)2 * KC * (BM + 32 + BN + 32) * sizeof(float); }
 
@@ -158,84 +215,217 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
         }
     };
     const int fcol = lane & 31, fk = wk * KW + (lane >> 5);
-    auto compute = [&](int buf) {
-        const float *Ab = As + (buf * KC + fk) * LDA + wm * TM * 32 + fcol;
-        const float *Bb = Bs + (buf * KC + fk) * LDB + wn * TN * 32 + fcol;
+    const float *const Ar = As + fk * LDA + wm * TM * 32 + fcol, *const Br = Bs + fk * LDB + wn * TN * 32 + fcol;
+    auto compute = [&](int buf) {   // fragments of step kk+1 are requested before the MFMAs of step kk
+        float a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = Ar[buf * KC * LDA + i * 32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = Br[buf * KC * LDB + j * 32];
 #pragma unroll
         for (int kk = 0; kk < KW / 2; ++kk) {
-            float a[TM], b[TN];
+            float an[TM], bn[TN];
+            if (kk + 1 < KW / 2) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = Ab[kk * 2 * LDA + i * 32];
+                for (int i = 0; i < TM; ++i) an[i] = Ar[(buf * KC + kk * 2 + 2) * LDA + i * 32];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = Bb[kk * 2 * LDB + j * 32];
+                for (int j = 0; j < TN; ++j) bn[j] = Br[(buf * KC + kk * 2 + 2) * LDB + j * 32];
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+            if (kk + 1 < KW / 2) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[i] = an[i];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[j] = bn[j];
+            }
+            // pin the order: the LDS reads of the next step, then this step's MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
         }
     };
 
+    // two chunks per loop pass with literal buffer numbers and no branch around the
+    // MFMAs (the accumulators stay in place); an odd chunk count is peeled off in front
+    const int odd = T & 1;
     gload(S0);          // chunk 0 (zeros when the segment is empty)
-    sstore(S0, 0);
+    if (odd) sstore(S0, 1); else sstore(S0, 0);
     __syncthreads();
-    for (int t = 0; t < T; ++t) {
-        gload(S0);      // chunk t+1; past the end of the segment every row is dead
-        compute(t & 1);
-        sstore(S0, (t + 1) & 1);
+    auto iteration = [&](int buf) {
+        gload(S0);      // next chunk; past the end of the segment every row is dead
+        compute(buf);
+        sstore(S0, buf ^ 1);
         __syncthreads();
+    };
+    if (odd) iteration(1);
+    for (int t = odd; t < T; t += 2) {
+        iteration(0);
+        iteration(1);
     }
 
-    // Add the WAVES_K partial tiles: in each round the upper half of the
-    // remaining waves hands its accumulators to the lower half through LDS.
-    if (WAVES_K > 1) {
-        float4 *red = reinterpret_cast<float4 *>(smem);
+    wgrad_tile_epilogue<TM, TN, WAVES_M, WAVES_N, WAVES_K>(acc, smem, P, z, tap, m0, n0, wm, wn, wk, lane);
+}
+
+// The same GEMM with the contraction index ordered (oh, ow) outer, batch n
+// inner: a K-chunk is KC consecutive images at one (oh,ow) of the tap's trimmed
+// range.  Then the address of a chunk is a per-lane constant (image and channel
+// of the lane) plus one scalar offset ((oh,ow) and first image of the chunk),
+// so the loop issues buffer loads with a scalar offset and no vector ALU
+// instruction for addressing -- VALU instructions and MFMAs of one SIMD do not
+// overlap, so each one removed from the loop is MFMA time won.  Needs N to be a
+// multiple of KC, 16-byte aligned tensors with channel counts that are
+// multiples of 4, and tensors below 2 GiB; the pixel-ordered kernel above
+// handles everything else.
+template <int BM, int BN, int KC, int WAVES_M, int WAVES_N, int WAVES_K>
+__global__ void __launch_bounds__(kThreads) pixel_gemm_fast(const PixelGemmParams P)
+{
+    constexpr int LDA = BM + 32, LDB = BN + 32;
+    constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
+    constexpr int PA = BM / 64, PB = BN / 64;
+    constexpr int PK = KC / 16;
+    constexpr int KW = KC / WAVES_K;
+    static_assert(WAVES_M * WAVES_N * WAVES_K == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1 && PK >= 1 &&
+                  KW % 2 == 0, "tile shape");
+
+    extern __shared__ __align__(16) float smem[];
+    float *As = smem;                 // [2][KC][LDA]   dY rows
+    float *Bs = smem + 2 * KC * LDA;  // [2][KC][LDB]   X rows
+
+    const int work = xcd_contiguous_work(blockIdx.x, P.perXcd);
+    if (work >= P.total) return;
+    const int nt = work % P.nTiles;
+    const int mt = (work / P.nTiles) % P.mTiles;
+    const int tap = (work / (P.nTiles * P.mTiles)) % (P.FH * P.FW);
+    const int z = work / (P.nTiles * P.mTiles * P.FH * P.FW);
+    const int fh = tap / P.FW, fw = tap - fh * P.FW;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    // Algorithm 3B: the (oh,ow) whose X element exists for this tap.
+    const int ih_s = fh - P.p, iw_s = fw - P.p;
+    const int oh_s = max(cdiv_any(-ih_s, P.s), 0), oh_e = min(P.OH, cdiv_any(P.IH - ih_s, P.s));
+    const int ow_s = max(cdiv_any(-iw_s, P.s), 0), ow_e = min(P.OW, cdiv_any(P.IW - iw_s, P.s));
+    const int nOH = max(oh_e - oh_s, 0), nOW = max(ow_e - ow_s, 0);
+    const int NC = P.N / KC;                       // chunks per (oh,ow)
+    const int Ct = nOH * nOW * NC;                 // chunks of this tap
+    const int seg = (Ct + P.GZ - 1) / P.GZ;
+    const int cbeg = min(z * seg, Ct), T = min(cbeg + seg, Ct) - cbeg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wk = wave % WAVES_K, wn = (wave / WAVES_K) % WAVES_N, wm = wave / (WAVES_K * WAVES_N);
+
+    // per-lane part of the addresses: image lr (+16, ...) of the chunk, channels lc (+64, ...)
+    const int lr = tid >> 4, lc = (tid & 15) * 4;
+    unsigned va[PK][PA], vb[PK][PB];
 #pragma unroll
-        for (int h = WAVES_K / 2; h >= 1; h /= 2) {
-            // slot of the (wm, wn, wk - h) tile: TM*TN*4 float4 per lane
-            if (wk >= h && wk < 2 * h) {
-                float4 *dst = red + (size_t)(((wm * WAVES_N + wn) * h + (wk - h)) * TM * TN * 4) * 64 + lane;
+    for (int r = 0; r < PK; ++r) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < PA; ++i)   // channels past the end are clamped (loaded twice, never stored)
+            va[r][i] = (unsigned)(((lr + 16 * r) * P.OH * P.OW * P.OC + min(m0 + lc + 64 * i, P.OC - 4)) * 4);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            dst[((i * TN + j) * 4 + q) * 64] = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
-                                                                           acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            }
-            __syncthreads();
-            if (wk < h) {
-                const float4 *src = red + (size_t)(((wm * WAVES_N + wn) * h + wk) * TM * TN * 4) * 64 + lane;
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float4 v = src[((i * TN + j) * 4 + q) * 64];
-                            acc[i][j][4 * q] += v.x;
-                            acc[i][j][4 * q + 1] += v.y;
-                            acc[i][j][4 * q + 2] += v.z;
-                            acc[i][j][4 * q + 3] += v.w;
-                        }
-            }
-            __syncthreads();
-        }
-        if (wk != 0) return;
+        for (int i = 0; i < PB; ++i)
+            vb[r][i] = (unsigned)(((lr + 16 * r) * P.IH * P.IW * P.IC + min(n0 + lc + 64 * i, P.IC - 4)) * 4);
+    }
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY), 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.X), 0, -1, 0x00020000);
+
+    // scalar part: position and first image of the chunk being loaded
+    int nch = 0, pa_ = 0, pb_ = 0;
+    if (T > 0) {
+        nch = cbeg % NC;
+        const int pos = cbeg / NC;
+        pa_ = pos / nOW;
+        pb_ = pos - pa_ * nOW;
     }
 
-    float *out = P.Out + (long)z * P.sliceElems;
+    floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int ic = n0 + (wn * TN + j) * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int oc = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (oc < P.OC && ic < P.IC) out[((long)oc * P.FH * P.FW + tap) * P.IC + ic] = acc[i][j][r];
-            }
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    struct Stage { float4 a[PK][PA], b[PK][PB]; };
+    Stage S0;
+    auto gload = [&](bool live) {
+        if (!live) return;   // uniform
+        const int oh = oh_s + pa_, ow = ow_s + pb_, n1 = nch * KC;
+        const int sa = (((n1 * P.OH + oh) * P.OW + ow) * P.OC) * 4;
+        const int sb = (((n1 * P.IH + oh * P.s + ih_s) * P.IW + ow * P.s + iw_s) * P.IC) * 4;
+#pragma unroll
+        for (int r = 0; r < PK; ++r) {
+#pragma unroll
+            for (int i = 0; i < PA; ++i)
+                S0.a[r][i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsA, va[r][i], sa, 0));
+#pragma unroll
+            for (int i = 0; i < PB; ++i)
+                S0.b[r][i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsB, vb[r][i], sb, 0));
         }
+        if (++nch == NC) { nch = 0; if (++pb_ == nOW) { pb_ = 0; ++pa_; } }
+    };
+    float *const Aw = As + lr * LDA + lc, *const Bw = Bs + lr * LDB + lc;
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < PK; ++r) {
+#pragma unroll
+            for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(Aw + (buf * KC + 16 * r) * LDA + 64 * i) = S0.a[r][i];
+#pragma unroll
+            for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(Bw + (buf * KC + 16 * r) * LDB + 64 * i) = S0.b[r][i];
+        }
+    };
+    const int fcol = lane & 31, fk = wk * KW + (lane >> 5);
+    const float *const Ar = As + fk * LDA + wm * TM * 32 + fcol, *const Br = Bs + fk * LDB + wn * TN * 32 + fcol;
+    auto compute = [&](int buf) {   // fragments of step kk+1 are requested before the MFMAs of step kk
+        float a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = Ar[buf * KC * LDA + i * 32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = Br[buf * KC * LDB + j * 32];
+#pragma unroll
+        for (int kk = 0; kk < KW / 2; ++kk) {
+            float an[TM], bn[TN];
+            if (kk + 1 < KW / 2) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) an[i] = Ar[(buf * KC + kk * 2 + 2) * LDA + i * 32];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bn[j] = Br[(buf * KC + kk * 2 + 2) * LDB + j * 32];
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+            if (kk + 1 < KW / 2) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[i] = an[i];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[j] = bn[j];
+            }
+            // pin the order: the LDS reads of the next step, then this step's MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+        }
+    };
+
+    // two chunks per loop pass with literal buffer numbers; an odd count is peeled off in front
+    const int odd = T & 1;
+    gload(T > 0);
+    if (T > 0) { if (odd) sstore(1); else sstore(0); }
+    __syncthreads();
+    auto iteration = [&](int t, int buf) {
+        gload(t + 1 < T);
+        compute(buf);
+        if (t + 1 < T) sstore(buf ^ 1);
+        __syncthreads();
+    };
+    if (odd) iteration(0, 1);
+    for (int t = odd; t < T; t += 2) {
+        iteration(t, 0);
+        iteration(t + 1, 1);
+    }
+
+    wgrad_tile_epilogue<TM, TN, WAVES_M, WAVES_N, WAVES_K>(acc, smem, P, z, tap, m0, n0, wm, wn, wk, lane);
 }
 
 // dW[e] = sum_z part[z][e] in a fixed association, so two runs agree bit for
