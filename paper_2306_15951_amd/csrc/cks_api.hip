@@ -203,8 +203,10 @@ WgradPlan plan_wgrad(const Geo &g)
             return w;
         }
     }
-    const bool bigM = g.OC >= 96, bigN = g.C >= 96;
-    w.variant = bigM && bigN ? 0 : (bigM ? 5 : (bigN ? 6 : 4));
+    // 64-wide channel tiles; 128 output channels per tile only when there are
+    // many tiles anyway (measured: 128x128 tiles lose 5-8 points on every layer)
+    const long long tiles64 = (long long)g.FH * g.FW * ((g.OC + 63) / 64) * ((g.C + 63) / 64);
+    w.variant = (g.OC >= 96 && tiles64 > 128) ? 5 : 4;
     long long gz_override = 0;
     if (const char *t = tune) {
         int v = -1, z = 0;
@@ -223,9 +225,9 @@ WgradPlan plan_wgrad(const Geo &g)
     // segments -- a multiple of 8 segments, so that every die works on whole
     // segments (measured: 8 segments beat 7 or 9 by 10-15 %).
     long long gz = 4LL * kCUs / tiles;
-    gz = gz < K / 256 ? gz : K / 256;
-    if (gz >= kXcds) gz = gz / kXcds * kXcds;
-    else if (K / 256 >= kXcds && tiles * kXcds <= 8LL * kCUs) gz = kXcds;
+    if (gz >= kXcds) gz = (gz + kXcds / 2) / kXcds * kXcds;
+    else if (tiles * kXcds <= 16LL * kCUs) gz = kXcds;
+    while (gz > 1 && K / gz < 256) gz = gz > kXcds ? gz - kXcds : gz / 2;
     if (gz < 1) gz = 1;
     if (gz_override > 0) gz = gz_override;
     if (gz < 1) gz = 1;
