@@ -6,6 +6,9 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
+#include <set>
+#include <utility>
 
 #include "cks_pack.h"
 #include "cks_patch_fwd.h"
@@ -47,12 +50,29 @@ inline int hip_fail(hipError_t e)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Kernels that need more than 64 KB of dynamic LDS must be told so once per
+// device; the call is a driver round trip, so the (kernel, device) pairs already
+// configured (for the full 160 KB) are remembered.
+inline hipError_t allow_large_lds(const void *kernel)
+{
+    static std::mutex mu;
+    static std::set<std::pair<const void *, int>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({kernel, dev})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess) done.insert({kernel, dev});
+    return e;
+}
+
 template <typename K, typename P>
 int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st, int threads = kThreads)
 {
+    if (lds > 160 * 1024) return CKS_ERR_SHAPE;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel));
         if (e != hipSuccess) return hip_fail(e);
     }
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), lds, st, params);
@@ -343,7 +363,8 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
     // Image stems (very few input channels): one GEMM over all pixels with the
     // whole filter patch as contraction axis and the filter resident in LDS.
     const int KP = (FH * FW * C + 15) / 16 * 16;
-    if (C < 8 && KP <= kPatchFwdMaxKP && (long long)H * W * C * (18 / ((long long)g.OH * g.OW) + 2) < (1LL << 29) && !getenv("CKS_TUNE_NO_PATCH_FWD")) {
+    if (C < 8 && KP <= kPatchFwdMaxKP && (long long)N * H * W * C * 4 < (1LL << 31) &&
+        (long long)N * g.OH * g.OW * OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_PATCH_FWD")) {
         PatchFwdParams Q{};
         Q.X = X; Q.W = Wt; Q.Y = Y;
         Q.N = N; Q.IC = C; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW;

@@ -63,56 +63,72 @@ __global__ void __launch_bounds__(kPatchFwdThreads) patch_fwd(const PatchFwdPara
         if (oc0 + r < P.OC) Ws[r * LDK + j] = P.W[(long)(oc0 + r) * J + j];
     }
 
+    // X as a raw buffer of its exact size (the host checks that X and Y are below
+    // 2 GiB): an offset of 2 GiB is out of range whatever scalar offset is added.
+    const int img = P.IH * P.IW * P.IC;   // floats per image
+    const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.X), 0, P.N * img * 4, 0x00020000);
+    constexpr int kBeyond = (int)0x80000000u;
+
     if (wave >= 4) {
-        // ---------------- staging waves: wave pw fetches pixels 16pw .. 16pw+15 of a tile
+        // ---------------- staging waves: wave pw fetches pixels 16pw .. 16pw+15 of a tile.
+        // Lane l handles patch columns j' = l, l+64, l+128.  A group of 16 pixels
+        // whose patches lie wholly inside X and in one image row is fetched with
+        // buffer loads "lane constant + scalar pixel offset": no vector ALU work.
         const int pw = wave - 4;
-        unsigned col_off[PASSES];
-        int col_fh[PASSES], col_j[PASSES];   // patch columns of this lane: j' = lane + 64*q
+        int col_off[PASSES], col_fh[PASSES], col_j[PASSES];
 #pragma unroll
         for (int q = 0; q < PASSES; ++q) {
             const int jf = lane + 64 * q;
             if (jf < J) {
                 col_fh[q] = jf / L;
                 col_j[q] = jf - col_fh[q] * L;
-                col_off[q] = (unsigned)(col_fh[q] * P.IW * P.IC + col_j[q]);
+                col_off[q] = col_fh[q] * P.IW * P.IC + col_j[q];
             } else {
                 col_fh[q] = 1 << 20;   // never inside a patch
                 col_j[q] = 0;
-                col_off[q] = 0;
+                col_off[q] = 0;        // reads element 0 of the patch; never staged
             }
         }
         float stage[16][PASSES];
-        const int img = P.IH * P.IW * P.IC;   // floats per image (the host checks that offsets below fit 32 bits)
         auto fetch = [&](int tile, int buf) {
-            // Lane l (mod 16) describes pixel 16pw + l of the tile: where its patch
-            // starts relative to the first pixel's image, and which filter rows /
-            // columns of it lie inside X.  The descriptors are then read lane by
-            // lane into scalar registers, so the 48 loads below need no branches
-            // and one scalar base address.
+            if (tile >= tile_end) return;   // uniform
             const int m0 = tile * 64 + pw * 16;
-            const int nb = (m0 < M ? m0 : 0) / (P.OH * P.OW);   // image of the first pixel (wave-uniform)
-            const int mp = m0 + (lane & 15);
-            const bool live = tile < tile_end && mp < M;
-            const int ow = mp % P.OW, t2 = mp / P.OW, oh = t2 % P.OH, n = t2 / P.OH;
+            int ow = m0 % P.OW;
+            const int t2 = m0 / P.OW;
+            int oh = t2 % P.OH;
+            int n = t2 / P.OH;
             const int ih0 = oh * P.s - P.p, iw0 = ow * P.s - P.p;
-            const int d_off = live ? (n - nb) * img + (ih0 * P.IW + iw0) * P.IC : 0;
-            const int d_fh_lo = max(-ih0, 0), d_j_lo = max(-iw0, 0) * P.IC;
-            // valid extents clamped at 0: a window wholly in the padding must not become a huge unsigned range
-            const int d_fh_n = live ? max(min(P.IH - ih0, P.FH) - d_fh_lo, 0) : 0;
-            const int d_j_n = max(min(P.IW - iw0, P.FW) * P.IC - d_j_lo, 0);
-            const char *xb = reinterpret_cast<const char *>(P.X + (long)nb * img);
+            const bool fast = m0 + 16 <= M && ow + 16 <= P.OW && ih0 >= 0 && ih0 + P.FH <= P.IH && iw0 >= 0 &&
+                              iw0 + 15 * P.s + P.FW <= P.IW;
+            if (fast) {
+                const int s0 = ((n * P.IH + ih0) * P.IW + iw0) * P.IC * 4, ds = P.s * P.IC * 4;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int off = __builtin_amdgcn_readlane(d_off, i);
-                const int fh_lo = __builtin_amdgcn_readlane(d_fh_lo, i), fh_n = __builtin_amdgcn_readlane(d_fh_n, i);
-                const int j_lo = __builtin_amdgcn_readlane(d_j_lo, i), j_n = __builtin_amdgcn_readlane(d_j_n, i);
+                for (int i = 0; i < 16; ++i)
 #pragma unroll
-                for (int q = 0; q < PASSES; ++q) {
-                    const bool ok = ((unsigned)(col_fh[q] - fh_lo) < (unsigned)fh_n) & ((unsigned)(col_j[q] - j_lo) < (unsigned)j_n);
-                    // a tap in the padding (or a dead pixel) reads byte 0 of the image instead and is zeroed
-                    const unsigned boff = ok ? (unsigned)(off + (int)col_off[q]) * 4u : 0u;
-                    const float v = *reinterpret_cast<const float *>(xb + boff);
-                    stage[i][q] = ok ? v : 0.f;
+                    for (int q = 0; q < PASSES; ++q)
+                        stage[i][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsX, col_off[q] * 4, s0 + i * ds, 0));
+            } else {
+                // Border group: per pixel the valid filter rows / columns are scalar
+                // ranges; a lane whose tap is in the padding (or whose pixel is past
+                // the end) sends an offset beyond the descriptor's size, for which a
+                // buffer load returns zero without touching memory.  No branches, so
+                // all 48 loads are in flight together.
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const bool live = m0 + i < M;
+                    const int h0 = oh * P.s - P.p, w0 = ow * P.s - P.p;
+                    const int corner4 = (h0 * P.IW + w0) * P.IC * 4;   // may be negative
+                    const int fh_lo = max(-h0, 0), j_lo = max(-w0, 0) * P.IC;
+                    const unsigned fh_n = live ? (unsigned)max(min(P.IH - h0, P.FH) - fh_lo, 0) : 0u;
+                    const unsigned j_n = (unsigned)max(min(P.IW - w0, P.FW) * P.IC - j_lo, 0);
+                    const int sn = (live ? n : 0) * img * 4;
+#pragma unroll
+                    for (int q = 0; q < PASSES; ++q) {
+                        const bool ok = ((unsigned)(col_fh[q] - fh_lo) < fh_n) & ((unsigned)(col_j[q] - j_lo) < j_n);
+                        const int voff = ok ? corner4 + col_off[q] * 4 : kBeyond;
+                        stage[i][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsX, voff, sn, 0));
+                    }
+                    if (++ow == P.OW) { ow = 0; if (++oh == P.OH) { oh = 0; ++n; } }
                 }
             }
 #pragma unroll
@@ -137,6 +153,9 @@ __global__ void __launch_bounds__(kPatchFwdThreads) patch_fwd(const PatchFwdPara
     const int wm = wave >> 1, wn = wave & 1;
     const int frow = lane & 31, fk = (lane >> 5) * 4;
     const int nks = P.KP >> 3;   // even: KP is a multiple of 16
+    const __amdgpu_buffer_rsrc_t rsY = __builtin_amdgcn_make_buffer_rsrc(P.Y, 0, -1, 0x00020000);
+    const int col = oc0 + wn * 32 + (lane & 31);
+    const int vrow0 = wm * 32 + 4 * (lane >> 5);
     __syncthreads();
     for (int tile = tile_beg; tile < tile_end; ++tile) {
         const int buf = (tile - tile_beg) & 1;
@@ -163,11 +182,20 @@ __global__ void __launch_bounds__(kPatchFwdThreads) patch_fwd(const PatchFwdPara
             acc = mfma32(a1.z, b1.z, acc);
             acc = mfma32(a1.w, b1.w, acc);
         }
-        const int col = oc0 + wn * 32 + (lane & 31);
+        // a full tile is stored with "lane constant + scalar tile offset" addressing
+        const bool full = tile * 64 + 64 <= M && oc0 + 64 <= P.OC;   // uniform
+        if (full) {
+            const int st = tile * 64 * P.OC * 4;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = tile * 64 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (row < M && col < P.OC) P.Y[(long)row * P.OC + col] = acc[r];
+            for (int r = 0; r < 16; ++r)
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[r]), rsY,
+                                                      ((vrow0 + 8 * (r >> 2) + (r & 3)) * P.OC + col) * 4, st, 0);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile * 64 + vrow0 + 8 * (r >> 2) + (r & 3);
+                if (row < M && col < P.OC) P.Y[(long)row * P.OC + col] = acc[r];
+            }
         }
         __syncthreads();
     }
