@@ -15,6 +15,7 @@
 #include "cks_patch_gemm.h"
 #include "cks_pixel_gemm.h"
 #include "cks_rowrun_gemm.h"
+#include "cks_scatter_deconv.h"
 
 namespace {
 
@@ -329,11 +330,50 @@ size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride)
     return split_bytes(C, OC, FH, FW, stride);
 }
 
+// Few-channel KS-deconv (tap-stationary GEMM + LDS composing): geometry limits of scatter_deconv.
+struct ScatterPlan {
+    bool ok;
+    int NB;             // 16-column blocks (template parameter to use)
+    ScatterDeconvParams P;
+    size_t headBytes;
+};
+
+static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    ScatterPlan S{};
+    const int J = FH * FW * C, sic = stride * C;
+    if (C >= 8 || OC > 64 || OC % 4 != 0 || J > 160) return S;
+    ScatterDeconvParams &P = S.P;
+    P.N = N; P.IC = C; P.IH = H; P.IW = W; P.OC = OC; P.OH = g.OH; P.OW = g.OW;
+    P.FH = FH; P.FW = FW; P.s = stride; P.p = padding;
+    P.nBands = (g.OW + 15) / 16;
+    P.nTiles = (g.OH + 3) / 4;
+    P.OVF = (FW > stride ? FW - stride : 0) * C;
+    P.SW = 16 * sic + P.OVF;
+    const int touched = (15 * stride + FW) * C;
+    const int rest = (W + padding) * C - 16 * (P.nBands - 1) * sic;   // dX floats from the last band's start to the row's end
+    P.SWlast = touched > rest ? touched : rest;
+    if (P.SW > kScatterRP || P.SWlast > kScatterRP || touched > kScatterRP) return S;
+    if ((FW + stride - 1) / stride > kScatterMaxTB) return S;
+    P.slots = 8 + (FH - 1) / stride;   // rows being composed (4) + rows being produced (4) + history
+    const int rowsEnd = (4 * P.nTiles - 1) * stride + FH, rowsImg = H + padding;
+    P.nFlush = ((rowsEnd > rowsImg ? rowsEnd : rowsImg) + 4 * stride - 1) / (4 * stride);
+    P.KP = (OC + 15) / 16 * 16;
+    S.NB = J <= 64 ? 4 : 10;
+    if (scatter_deconv_lds_bytes(S.NB, P.slots, FH) > 160 * 1024) return S;
+    if (!fits_i31((long long)N * P.nBands)) return S;
+    S.headBytes = (size_t)N * (P.nBands - 1) * H * P.OVF * sizeof(float);
+    S.ok = true;
+    return S;
+}
+
 size_t cks_deconv2d_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
 {
     Geo g;
     if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
-    return split_bytes(C, OC, FH, FW, stride);
+    const size_t split = split_bytes(C, OC, FH, FW, stride);
+    const ScatterPlan S = plan_scatter(g, N, C, H, W, OC, FH, FW, stride, padding);
+    return S.ok && S.headBytes > split ? S.headBytes : split;
 }
 
 int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
@@ -420,7 +460,26 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
     if (rc != CKS_OK) return rc;
     if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!dY || !Wt || !dX) return CKS_ERR_NULL;
-    if (!ws || ws_bytes < split_bytes(C, OC, FH, FW, stride)) return CKS_ERR_WORKSPACE;
+    if (!ws || ws_bytes < cks_deconv2d_workspace(N, C, H, W, OC, FH, FW, stride, padding)) return CKS_ERR_WORKSPACE;
+    ScatterPlan S = plan_scatter(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (S.ok && aligned16(dY) && aligned16(ws) && !getenv("CKS_TUNE_NO_SCATTER")) {
+        hipStream_t st = (hipStream_t)stream;
+        S.P.dY = dY; S.P.W = Wt; S.P.dX = dX; S.P.head = (float *)ws;
+        const int blocks = N * S.P.nBands;
+        const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
+        const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2;
+        if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, blocks, lds, st, kScatterThreads);
+        else if (stem) rc = launch(scatter_deconv<10, true>, S.P, blocks, lds, st, kScatterThreads);
+        else rc = launch(scatter_deconv<10, false>, S.P, blocks, lds, st, kScatterThreads);
+        if (rc != CKS_OK || S.headBytes == 0) return rc;
+        BandHeadParams B{};
+        B.head = (const float *)ws; B.dX = dX;
+        B.N = N; B.IC = C; B.IH = H; B.IW = W; B.s = stride; B.p = padding; B.nBands = S.P.nBands; B.OVF = S.P.OVF;
+        B.total = (long)(S.headBytes / sizeof(float));
+        const long long hb = (B.total + kThreads - 1) / kThreads;
+        if (!fits_i31(hb)) return CKS_ERR_SHAPE;
+        return launch(add_band_heads, B, (int)hb, 0, st);
+    }
     rc = cks_kernel_split(Wt, (float *)ws, C, OC, FH, FW, stride, stream);
     if (rc != CKS_OK) return rc;
     return cks_deconv2d_presplit(dY, (const float *)ws, dX, N, C, H, W, OC, FH, FW, stride, padding, stream);

@@ -1,0 +1,240 @@
+// KS-deconv for layers with few input channels (image stems).
+//
+// Kernel split turns the input gradient into stride^2 small convolutions whose
+// GEMMs have IC output columns each; with IC = 3 an MFMA tile would be 9 % full.
+// This kernel therefore keeps the sub-kernels' arithmetic (only real filter taps
+// meet real dY elements; no zero of the dilated dY is ever touched) but runs it
+// tap-stationary: for a row of 16 dY pixels
+//     P[ow, (fh,fw,ic)] = sum_oc dY[n,oh,ow,oc] * W[oc,fh,fw,ic]
+// is one dense GEMM (rows = pixels, columns = J = FH*FW*IC, K = OC), and the
+// composing phase of the paper's Stage 3 is
+//     dX[n, oh*s-p+fh, ow*s-p+fw, ic] = sum over the (oh,fh), (ow,fw) that map there of P.
+// Columns with equal (fh mod s, fw mod s) are one sub-kernel; their targets
+// interleave exactly as the sub-kernels' outputs do.  The sum is separable and is
+// taken in two steps, both in a fixed order (the result does not depend on timing):
+//   1. along the row:  Q[oh][fh][x] = sum_{tb} P[v-tb, (fh, b+s*tb, ic)] for ring
+//      float x = (v*s+b)*IC+ic, by the wave that computed P, through a wave-private
+//      LDS scratch (the MFMA result layout has the addends in different lanes);
+//   2. across rows:    dX row (ih+p) = sum_{fh = (ih+p) mod s, +s, ...} Q[(ih+p-fh)/s][fh],
+//      by the staging waves when the sweep has passed the row, from a ring of Q rows.
+// A workgroup owns one image and a band of 16 dY columns and sweeps it top to
+// bottom, four dY rows (one per MFMA wave) per step.  Neighbouring bands overlap
+// in (FW - s) dX pixel columns: a band writes its share of the columns it has in
+// common with its left neighbour to a small side buffer, and add_band_heads adds
+// that to dX afterwards, so no two workgroups ever add to one address.
+//
+// Every global access is a buffer access "lane constant + scalar" against a
+// per-row descriptor: rows and pixels outside the tensors fall outside the
+// descriptor and read as zero or are dropped on store.
+#pragma once
+#include "cks_device.h"
+
+namespace cks {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct ScatterDeconvParams {
+    const float *dY;
+    const float *W;     // OHWI
+    float *dX;
+    float *head;        // [N][nBands-1][IH][OVF]
+    int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
+    int nBands;         // ceil(OW / 16)
+    int nTiles;         // ceil(OH / 4)
+    int nFlush;         // output steps of 4*s dX rows each
+    int SW;             // floats of a dX row a band writes (from its first touched float)
+    int SWlast;         // the same for the last band (includes dX columns no pixel reaches)
+    int OVF;            // floats per row shared with the left neighbour: max(FW - s, 0) * IC
+    int slots;          // Q ring: dY rows kept
+    int KP;             // OC rounded up to 16
+};
+
+constexpr int kScatterThreads = 512;
+constexpr int kScatterLDK = 68;    // K <= 64, +4 keeps 16-row fragments conflict free
+constexpr int kScatterPP = 20;     // scratch floats per column: 16 pixels + 4 (bank skew, keeps float4 alignment)
+constexpr int kScatterRP = 128;    // floats per Q row
+constexpr int kScatterMaxTB = 4;   // taps per sub-kernel row: ceil(FW / s) <= 4
+inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
+{
+    return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + (size_t)slots * FH * kScatterRP) * sizeof(float);
+}
+
+// NB: 16-column blocks of the GEMM (J <= 16 NB).  STEM: the geometry is the
+// 7x7 / stride 2 / 3-channel stem, known at compile time, so that every LDS
+// access of the composing steps is "lane constant + immediate".
+template <int NB, bool STEM>
+__global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterDeconvParams P)
+{
+    constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
+    constexpr int kBeyond = (int)0x80000000u;   // an offset outside every descriptor used here
+    const int FH = STEM ? 7 : P.FH, FW = STEM ? 7 : P.FW, IC = STEM ? 3 : P.IC, S = STEM ? 2 : P.s;
+    extern __shared__ __align__(16) float smem[];
+    float *Bs = smem;                           // [NB*16][LDK]       filter, column-major: Bs[j'][oc]
+    float *Ps = Bs + NB * 16 * LDK;             // [4][NB*16][PP]     per-wave P scratch
+    float *Qs = Ps + 4 * NB * 16 * PP;          // [slots][FH][RP]    ring of row-composed dY rows
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = blockIdx.x / P.nBands, c = blockIdx.x - n * P.nBands;
+    const int ow0 = c * 16;
+    const int L = FW * IC, J = FH * L;
+    const int rows4s = 4 * S;
+
+    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + P.slots * FH * RP;
+    for (int i = tid; i < ldsFloats; i += kScatterThreads) smem[i] = 0.f;
+    __syncthreads();
+    for (int i = tid; i < P.OC * J; i += kScatterThreads) {
+        const int oc = i / J, j = i - oc * J;
+        Bs[j * LDK + oc] = P.W[i];
+    }
+    __syncthreads();
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ staging waves: step 2 and the stores
+        const int pw = wave - 4;
+        // Q float x of this band is dX float (ow0*s - p)*IC + x of its image row.
+        const int sw = c == P.nBands - 1 ? P.SWlast : P.SW;
+        const int x0 = (ow0 * S - P.p) * IC;
+        int voffX[2], voffH[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int x = lane + 64 * q;
+            const bool mine = x < sw && !(c > 0 && x < P.OVF);
+            voffX[q] = mine ? (x0 + x) * 4 : kBeyond;   // negative (left padding) is out of range as well
+            voffH[q] = (c > 0 && x < P.OVF) ? x * 4 : kBeyond;
+        }
+        for (int i = 0; i <= P.nFlush; ++i) {
+            const int k = i - 1;   // rows [k*4s, (k+1)*4s) are complete once tile k is done
+            if (k >= 0 && k < P.nFlush) {
+                for (int r = pw; r < rows4s; r += 4) {
+                    const int row = k * rows4s + r;   // = ih + p
+                    const int ih = row - P.p;
+                    const bool in = ih >= 0 && ih < P.IH;   // uniform
+                    if (!in) continue;
+                    float sum0 = 0.f, sum1 = 0.f;
+                    for (int fh = row % S; fh < FH; fh += S) {
+                        const int oh = (row - fh) / S;   // row >= fh is checked first
+                        if (row < fh || oh >= P.OH) continue;
+                        const float *qp = Qs + ((oh % P.slots) * FH + fh) * RP + lane;
+                        sum0 += qp[0];
+                        sum1 += qp[64];
+                    }
+                    const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc(
+                        P.dX + ((long)n * P.IH + ih) * P.IW * IC, 0, P.IW * IC * 4, 0x00020000);
+                    const __amdgpu_buffer_rsrc_t rsH = __builtin_amdgcn_make_buffer_rsrc(
+                        P.head + (((long)n * (P.nBands - 1) + max(c - 1, 0)) * P.IH + ih) * P.OVF, 0,
+                        c > 0 ? P.OVF * 4 : 0, 0x00020000);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsX, voffX[0], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsX, voffX[1], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsH, voffH[0], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsH, voffH[1], 0, 0);
+                }
+            }
+            __syncthreads();
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- MFMA waves: wave w owns dY row 4i + w of step i
+    // 16x16x4 MFMA: lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16];
+    // result register r holds D[m = 4*(l/16) + r][n = l%16].
+    const int lm = lane & 15, lk = lane >> 4;
+    const int KU = P.KP >> 4;
+    // A straight from global: pixel lm, channels 16u + 4lk .. +3 (channels past OC are out of range)
+    int a_voff[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a_voff[u] = (16 * u + 4 * lk < P.OC) ? (lm * P.OC + 16 * u + 4 * lk) * 4 : kBeyond;
+    const int a_bytes = min(16, P.OW - ow0) * P.OC * 4;
+    float4 areg[4];
+    auto fetch = [&](int i) {
+        const int oh = 4 * i + wave;
+        const long off = (((long)n * P.OH + min(oh, P.OH - 1)) * P.OW + ow0) * P.OC;
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + off), 0, oh < P.OH ? a_bytes : 0, 0x00020000);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            areg[u] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff[u], 0, 0));
+    };
+    // step 1, lane constants: ring float x = lane + 64q is pixel column pwx = x / IC (= v*s + b), channel ic
+    float *Pw = Ps + wave * NB * 16 * PP;
+    const float *gat[2];
+    bool tap_ok[2][MAXTB];
+    const int touched = (15 * S + FW) * IC;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int x = lane + 64 * q;
+        const int pwx = x / IC, ic = x - pwx * IC, b = pwx % S, v = pwx / S;
+        gat[q] = Pw + (b * IC + ic) * PP + v;   // column (fh=0, fw=b, ic), pixel v; + fh*L*PP + tb*(s*IC*PP - 1)
+#pragma unroll
+        for (int tb = 0; tb < MAXTB; ++tb) tap_ok[q][tb] = x < touched && b + S * tb < FW && v - tb >= 0 && v - tb < 16;
+    }
+    const int fhStride = L * PP, tbStride = S * IC * PP - 1;
+    float *Pst = Pw + lm * PP + 4 * lk;   // + b*16*PP: P[pixels 4lk..4lk+3][column 16b + lm]
+    const float *Bp = Bs + lm * LDK + 4 * lk;
+
+    fetch(0);
+    for (int i = 0; i <= P.nFlush; ++i) {
+        if (i < P.nTiles) {   // uniform
+            floatx4 acc[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+            float4 a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = areg[u];
+            if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (u < KU) {
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const float4 w4 = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * u);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, w4.x, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, w4.y, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, w4.z, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, w4.w, acc[b], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+            // the scratch is private to this wave: its LDS accesses complete in order
+            float *qrow = Qs + (((4 * i + wave) % P.slots) * FH) * RP + lane;
+            for (int fh = 0; fh < FH; ++fh) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int tb = 0; tb < MAXTB; ++tb)
+                        if (tap_ok[q][tb]) sum += gat[q][fh * fhStride + tb * tbStride];
+                    qrow[fh * RP + 64 * q] = sum;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// dX[n, ih, (16 c s - p)*IC + x] += head[n][c-1][ih][x] for every band c >= 1.
+struct BandHeadParams {
+    const float *head;
+    float *dX;
+    int N, IC, IH, IW, s, p, nBands, OVF;
+    long total;   // N * (nBands-1) * IH * OVF
+};
+
+__global__ void __launch_bounds__(kThreads) add_band_heads(const BandHeadParams P)
+{
+    const long i = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= P.total) return;
+    const int x = (int)(i % P.OVF);
+    long t = i / P.OVF;
+    const int ih = (int)(t % P.IH);
+    t /= P.IH;
+    const int c = (int)(t % (P.nBands - 1)) + 1, n = (int)(t / (P.nBands - 1));
+    const int col = (16 * c * P.s - P.p) * P.IC + x;
+    if (col < 0 || col >= P.IW * P.IC) return;
+    P.dX[((long)n * P.IH + ih) * P.IW * P.IC + col] += P.head[i];
+}
+
+}  // namespace cks
