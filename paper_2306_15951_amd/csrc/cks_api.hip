@@ -343,6 +343,7 @@ static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC
     ScatterPlan S{};
     const int J = FH * FW * C, sic = stride * C;
     if (C >= 8 || OC > 64 || OC % 4 != 0 || J > 160) return S;
+    if ((long long)H * W * C * 4 >= (1LL << 31)) return S;   // an image is one raw buffer
     ScatterDeconvParams &P = S.P;
     P.N = N; P.IC = C; P.IH = H; P.IW = W; P.OC = OC; P.OH = g.OH; P.OW = g.OW;
     P.FH = FH; P.FW = FW; P.s = stride; P.p = padding;
@@ -354,7 +355,7 @@ static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC
     const int rest = (W + padding) * C - 16 * (P.nBands - 1) * sic;   // dX floats from the last band's start to the row's end
     P.SWlast = touched > rest ? touched : rest;
     if (P.SW > kScatterRP || P.SWlast > kScatterRP || touched > kScatterRP) return S;
-    if ((FW + stride - 1) / stride > kScatterMaxTB) return S;
+    if ((FW + stride - 1) / stride > kScatterMaxTB || (FH + stride - 1) / stride > kScatterMaxTB) return S;
     P.slots = 8 + (FH - 1) / stride;   // rows being composed (4) + rows being produced (4) + history
     const int rowsEnd = (4 * P.nTiles - 1) * stride + FH, rowsImg = H + padding;
     P.nFlush = ((rowsEnd > rowsImg ? rowsEnd : rowsImg) + 4 * stride - 1) / (4 * stride);
@@ -467,7 +468,7 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
         S.P.dY = dY; S.P.W = Wt; S.P.dX = dX; S.P.head = (float *)ws;
         const int blocks = N * S.P.nBands;
         const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
-        const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2;
+        const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2 && OC == 64;
         if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, blocks, lds, st, kScatterThreads);
         else if (stem) rc = launch(scatter_deconv<10, true>, S.P, blocks, lds, st, kScatterThreads);
         else rc = launch(scatter_deconv<10, false>, S.P, blocks, lds, st, kScatterThreads);

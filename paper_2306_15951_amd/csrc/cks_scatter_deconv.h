@@ -53,10 +53,10 @@ constexpr int kScatterThreads = 512;
 constexpr int kScatterLDK = 68;    // K <= 64, +4 keeps 16-row fragments conflict free
 constexpr int kScatterPP = 20;     // scratch floats per column: 16 pixels + 4 (bank skew, keeps float4 alignment)
 constexpr int kScatterRP = 128;    // floats per Q row
-constexpr int kScatterMaxTB = 4;   // taps per sub-kernel row: ceil(FW / s) <= 4
+constexpr int kScatterMaxTB = 4;   // taps per sub-kernel row and column: ceil(FW / s), ceil(FH / s) <= 4
 inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 {
-    return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + (size_t)slots * FH * kScatterRP) * sizeof(float);
+    return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + ((size_t)slots * FH + 1) * kScatterRP) * sizeof(float);
 }
 
 // NB: 16-column blocks of the GEMM (J <= 16 NB).  STEM: the geometry is the
@@ -68,10 +68,12 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
     constexpr int kBeyond = (int)0x80000000u;   // an offset outside every descriptor used here
     const int FH = STEM ? 7 : P.FH, FW = STEM ? 7 : P.FW, IC = STEM ? 3 : P.IC, S = STEM ? 2 : P.s;
+    const int SLOTS = STEM ? 11 : P.slots;   // 8 + (FH-1)/s
     extern __shared__ __align__(16) float smem[];
     float *Bs = smem;                           // [NB*16][LDK]       filter, column-major: Bs[j'][oc]
     float *Ps = Bs + NB * 16 * LDK;             // [4][NB*16][PP]     per-wave P scratch
     float *Qs = Ps + 4 * NB * 16 * PP;          // [slots][FH][RP]    ring of row-composed dY rows
+    const float *Qzero = Qs + SLOTS * FH * RP;   // [RP]               stays zero
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -80,7 +82,7 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     const int L = FW * IC, J = FH * L;
     const int rows4s = 4 * S;
 
-    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + P.slots * FH * RP;
+    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + (SLOTS * FH + 1) * RP;
     for (int i = tid; i < ldsFloats; i += kScatterThreads) smem[i] = 0.f;
     __syncthreads();
     for (int i = tid; i < P.OC * J; i += kScatterThreads) {
@@ -91,43 +93,58 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
 
     if (wave >= 4) {
         // ------------------------------------------------------------ staging waves: step 2 and the stores
+        // These waves issue few instructions, each of which would otherwise queue behind the MFMA
+        // wave of the same SIMD.
+        __builtin_amdgcn_s_setprio(3);
         const int pw = wave - 4;
-        // Q float x of this band is dX float (ow0*s - p)*IC + x of its image row.
+        // Q float x of this band is dX float (ow0*s - p)*IC + x of its image row.  The image (and this
+        // band's side buffer) is one raw buffer, the row a scalar offset; lanes outside the row or not
+        // written by this band carry an offset beyond it.
         const int sw = c == P.nBands - 1 ? P.SWlast : P.SW;
-        const int x0 = (ow0 * S - P.p) * IC;
+        const int x0 = (ow0 * S - P.p) * IC, rowFloats = P.IW * IC;
         int voffX[2], voffH[2];
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int x = lane + 64 * q;
-            const bool mine = x < sw && !(c > 0 && x < P.OVF);
-            voffX[q] = mine ? (x0 + x) * 4 : kBeyond;   // negative (left padding) is out of range as well
+            const bool mine = x < sw && !(c > 0 && x < P.OVF) && x0 + x >= 0 && x0 + x < rowFloats;
+            voffX[q] = mine ? (x0 + x) * 4 : kBeyond;
             voffH[q] = (c > 0 && x < P.OVF) ? x * 4 : kBeyond;
         }
-        for (int i = 0; i <= P.nFlush; ++i) {
-            const int k = i - 1;   // rows [k*4s, (k+1)*4s) are complete once tile k is done
+        const __amdgpu_buffer_rsrc_t rsX =
+            __builtin_amdgcn_make_buffer_rsrc(P.dX + (long)n * P.IH * rowFloats, 0, P.IH * rowFloats * 4, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsH = __builtin_amdgcn_make_buffer_rsrc(
+            P.head + ((long)n * (P.nBands - 1) + max(c - 1, 0)) * P.IH * P.OVF, 0, c > 0 ? P.IH * P.OVF * 4 : 0, 0x00020000);
+        // rows [k*4s, (k+1)*4s) are complete once step 1 of tile k is done: one pass after the tile's
+        // MFMAs, two where step 1 trails the MFMAs by a pass
+        constexpr int DELAY = STEM ? 2 : 1;
+        for (int i = 0; i < P.nFlush + DELAY; ++i) {
+            const int k = i - DELAY;
             if (k >= 0 && k < P.nFlush) {
+#pragma unroll 2
                 for (int r = pw; r < rows4s; r += 4) {
                     const int row = k * rows4s + r;   // = ih + p
                     const int ih = row - P.p;
-                    const bool in = ih >= 0 && ih < P.IH;   // uniform
-                    if (!in) continue;
-                    float sum0 = 0.f, sum1 = 0.f;
-                    for (int fh = row % S; fh < FH; fh += S) {
-                        const int oh = (row - fh) / S;   // row >= fh is checked first
-                        if (row < fh || oh >= P.OH) continue;
-                        const float *qp = Qs + ((oh % P.slots) * FH + fh) * RP + lane;
-                        sum0 += qp[0];
-                        sum1 += qp[64];
+                    if (ih < 0 || ih >= P.IH) continue;   // uniform
+                    // row = oh*s + fh: fh = r mod s + t*s, oh = 4k + r/s - t.  All reads are issued before the
+                    // first add; a term that does not exist reads the zero row behind the ring.
+                    const int fh0 = r % S, ohTop = 4 * k + r / S;
+                    float v0[MAXTB], v1[MAXTB];
+#pragma unroll
+                    for (int t = 0; t < MAXTB; ++t) {
+                        const int fh = fh0 + t * S, oh = ohTop - t;
+                        const bool ok = fh < FH && oh >= 0 && oh < P.OH;   // uniform
+                        const float *qp = (ok ? Qs + ((oh % SLOTS) * FH + fh) * RP : Qzero) + lane;
+                        v0[t] = qp[0];
+                        v1[t] = qp[64];
                     }
-                    const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc(
-                        P.dX + ((long)n * P.IH + ih) * P.IW * IC, 0, P.IW * IC * 4, 0x00020000);
-                    const __amdgpu_buffer_rsrc_t rsH = __builtin_amdgcn_make_buffer_rsrc(
-                        P.head + (((long)n * (P.nBands - 1) + max(c - 1, 0)) * P.IH + ih) * P.OVF, 0,
-                        c > 0 ? P.OVF * 4 : 0, 0x00020000);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsX, voffX[0], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsX, voffX[1], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsH, voffH[0], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsH, voffH[1], 0, 0);
+                    const float sum0 = (v0[0] + v0[1]) + (v0[2] + v0[3]);
+                    const float sum1 = (v1[0] + v1[1]) + (v1[2] + v1[3]);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsX, voffX[0], ih * rowFloats * 4, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsX, voffX[1], ih * rowFloats * 4, 0);
+                    if (c > 0) {
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsH, voffH[0], ih * P.OVF * 4, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsH, voffH[1], ih * P.OVF * 4, 0);
+                    }
                 }
             }
             __syncthreads();
@@ -157,61 +174,144 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     };
     // step 1, lane constants: ring float x = lane + 64q is pixel column pwx = x / IC (= v*s + b), channel ic
     float *Pw = Ps + wave * NB * 16 * PP;
-    const float *gat[2];
-    bool tap_ok[2][MAXTB];
+    const float *gat[2][MAXTB];
     const int touched = (15 * S + FW) * IC;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const int x = lane + 64 * q;
         const int pwx = x / IC, ic = x - pwx * IC, b = pwx % S, v = pwx / S;
-        gat[q] = Pw + (b * IC + ic) * PP + v;   // column (fh=0, fw=b, ic), pixel v; + fh*L*PP + tb*(s*IC*PP - 1)
 #pragma unroll
-        for (int tb = 0; tb < MAXTB; ++tb) tap_ok[q][tb] = x < touched && b + S * tb < FW && v - tb >= 0 && v - tb < 16;
+        for (int tb = 0; tb < MAXTB; ++tb) {
+            // column (fh=0, fw=b+s*tb, ic), pixel v-tb; + fh*L*PP selects the filter row.  A tap that does
+            // not exist reads pad slot 16 of column fh*L instead, which is never written and stays zero.
+            const bool ok = x < touched && b + S * tb < FW && v - tb >= 0 && v - tb < 16;
+            gat[q][tb] = ok ? Pw + ((b + S * tb) * IC + ic) * PP + v - tb : Pw + 16;
+        }
     }
-    const int fhStride = L * PP, tbStride = S * IC * PP - 1;
+    const int fhStride = L * PP;
     float *Pst = Pw + lm * PP + 4 * lk;   // + b*16*PP: P[pixels 4lk..4lk+3][column 16b + lm]
     const float *Bp = Bs + lm * LDK + 4 * lk;
 
     fetch(0);
-    for (int i = 0; i <= P.nFlush; ++i) {
-        if (i < P.nTiles) {   // uniform
-            floatx4 acc[NB];
+    if constexpr (STEM) {
+        // OC = 64: four K groups.  The filter fragments of group u+1 are requested before the MFMAs
+        // of group u are issued, and step 1 of the previous dY row (its P is still in the scratch,
+        // which is overwritten only after this row's MFMAs) rides along: its LDS reads join the
+        // fragment reads, its few adds fall between MFMAs.  The order is pinned; the compiler would
+        // otherwise sink every read to its use.
+        for (int i = 0; i <= P.nFlush + 1; ++i) {
+            // Q row of dY row 4(i-1) + wave; in the first pass the scratch is still all zero and the
+            // zero row receives zeros
+            float *qrow = (i > 0 ? Qs + (((4 * (i - 1) + wave) % SLOTS) * 7) * RP : Qs + SLOTS * 7 * RP) + lane;
+            if (i < P.nTiles) {   // uniform
+                floatx4 acc[NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-            float4 a[4];
+                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+                float4 a[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) a[u] = areg[u];
-            if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
+                for (int u = 0; u < 4; ++u) a[u] = areg[u];
+                if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
+                float4 wc[NB], wn[NB];
+                float g[7][2][MAXTB];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (u < KU) {
+                for (int b = 0; b < NB; ++b) wc[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK);
+                __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (u < 3) {
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) wn[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * (u + 1));
+                    }
+                    const int fhA = 2 * u, fhB = u < 3 ? 2 * u + 2 : 7;   // filter rows gathered alongside group u
+#pragma unroll
+                    for (int fh = fhA; fh < fhB; ++fh)
+#pragma unroll
+                        for (int q = 0; q < 2; ++q)
+#pragma unroll
+                            for (int tb = 0; tb < MAXTB; ++tb) g[fh][q][tb] = gat[q][tb][fh * fhStride];
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        const float4 w4 = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * u);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, w4.x, acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, w4.y, acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, w4.z, acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, w4.w, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, wc[b].x, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, wc[b].y, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, wc[b].z, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, wc[b].w, acc[b], 0, 0, 0);
+                    }
+                    // at most 15 LDS reads can be counted as outstanding: the fragment reads go first, the
+                    // gather reads follow in two batches once the group's MFMAs are under way
+                    if (u < 3) __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                    if (u < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * NB - 16, 0);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) wc[b] = wn[b];
+                }
+#pragma unroll
+                for (int fh = 0; fh < 7; ++fh)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+            } else if (i == P.nTiles) {
+                // the last dY rows: step 1 on its own
+                float g[7][2][MAXTB];
+#pragma unroll
+                for (int fh = 0; fh < 7; ++fh)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+#pragma unroll
+                        for (int tb = 0; tb < MAXTB; ++tb) g[fh][q][tb] = gat[q][tb][fh * fhStride];
+#pragma unroll
+                for (int fh = 0; fh < 7; ++fh)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+            }
+            __syncthreads();
+        }
+    } else {
+        for (int i = 0; i <= P.nFlush; ++i) {
+            if (i < P.nTiles) {   // uniform
+                floatx4 acc[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+                float4 a[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) a[u] = areg[u];
+                if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (u < KU) {
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) {
+                            const float4 w4 = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * u);
+                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, w4.x, acc[b], 0, 0, 0);
+                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, w4.y, acc[b], 0, 0, 0);
+                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, w4.z, acc[b], 0, 0, 0);
+                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, w4.w, acc[b], 0, 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+                // the scratch is private to this wave: its LDS accesses complete in order
+                float *qrow = Qs + (((4 * i + wave) % SLOTS) * FH) * RP + lane;
+                for (int fh = 0; fh < FH; ++fh) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int tb = 0; tb < MAXTB; ++tb) sum += gat[q][tb][fh * fhStride];
+                        qrow[fh * RP + 64 * q] = sum;
                     }
                 }
             }
-#pragma unroll
-            for (int b = 0; b < NB; ++b)
-                *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
-            // the scratch is private to this wave: its LDS accesses complete in order
-            float *qrow = Qs + (((4 * i + wave) % P.slots) * FH) * RP + lane;
-            for (int fh = 0; fh < FH; ++fh) {
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    float sum = 0.f;
-#pragma unroll
-                    for (int tb = 0; tb < MAXTB; ++tb)
-                        if (tap_ok[q][tb]) sum += gat[q][fh * fhStride + tb * tbStride];
-                    qrow[fh * RP + 64 * q] = sum;
-                }
-            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
