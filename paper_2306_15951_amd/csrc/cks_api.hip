@@ -16,6 +16,7 @@
 #include "cks_pixel_gemm.h"
 #include "cks_rowrun_gemm.h"
 #include "cks_scatter_deconv.h"
+#include "cks_strip_fwd.h"
 
 namespace {
 
@@ -404,6 +405,24 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
     // Image stems (very few input channels): one GEMM over all pixels with the
     // whole filter patch as contraction axis and the filter resident in LDS.
     const int KP = (FH * FW * C + 15) / 16 * 16;
+    // the 7x7 / stride 2 / 3-channel stem: input strip in LDS, addressing known at compile time
+    if (FH == 7 && FW == 7 && C == 3 && stride == 2 && (long long)H * W * C * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
+        using SG = StripGeo<7, 7, 3, 2>;
+        StripFwdParams Q{};
+        Q.X = X; Q.W = Wt; Q.Y = Y;
+        Q.N = N; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = padding;
+        Q.nBands = (g.OW + 15) / 16;
+        Q.nRowTiles = (g.OH + 3) / 4;
+        Q.nT = (OC + 63) / 64;
+        const long long tiles = (long long)N * Q.nBands * Q.nRowTiles;
+        if (fits_i31(tiles * Q.nT)) {
+            Q.tiles = (int)tiles;
+            const int groups = Q.tiles < 2 * kCUs ? Q.tiles : 2 * kCUs;   // two workgroups per compute unit
+            Q.tilesPerBlock = (Q.tiles + groups - 1) / groups;
+            const int blocks = ((Q.tiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
+            return launch(strip_fwd<7, 7, 3, 2>, Q, blocks, SG::lds_bytes(), (hipStream_t)stream, kStripThreads);
+        }
+    }
     if (C < 8 && KP <= kPatchFwdMaxKP && (long long)N * H * W * C * 4 < (1LL << 31) &&
         (long long)N * g.OH * g.OW * OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_PATCH_FWD")) {
         PatchFwdParams Q{};
