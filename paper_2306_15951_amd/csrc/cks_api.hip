@@ -17,6 +17,7 @@
 #include "cks_rowrun_gemm.h"
 #include "cks_scatter_deconv.h"
 #include "cks_strip_fwd.h"
+#include "cks_strip_wgrad.h"
 
 namespace {
 
@@ -178,8 +179,10 @@ int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int 
 
 // ---------------------------------------------------------------- Sk-dilated
 
+constexpr int kStripWgradGroups = kCUs;   // strip_wgrad: one workgroup (= one segment) per compute unit
+
 struct WgradPlan {
-    int patch;    // 0: one tile per filter tap (pixel_gemm); 1..3: all taps in one tile (patch_gemm), see below
+    int patch;    // 0: one tile per filter tap (pixel_gemm); 1..3: all taps in one tile (patch_gemm); 4: strip_wgrad
     int variant, bm, bn, mTiles, nTiles, GZ;
 };
 
@@ -205,6 +208,21 @@ WgradPlan plan_wgrad(const Geo &g)
     // Put the whole filter patch (J = FH*FW*IC columns) into one tile if it
     // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
     const long long J = (long long)g.FH * g.FW * g.C;
+    // the 7x7 / stride 2 / 3-channel stem: input strip in LDS (strip_wgrad), one segment per workgroup
+    if (g.FH == 7 && g.FW == 7 && g.C == 3 && g.s == 2 && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
+        !tune && !getenv("CKS_TUNE_NO_STRIP_WGRAD")) {
+        const long long tiles = (long long)g.N * ((g.OW + 15) / 16) * ((g.OH + 3) / 4);
+        if (fits_i31(tiles)) {
+            w.patch = 4;
+            w.variant = -1;
+            w.bm = 64; w.bn = 160;
+            w.mTiles = 1; w.nTiles = 1;
+            const int groups = tiles < kStripWgradGroups ? (int)tiles : kStripWgradGroups;
+            const int per = (int)((tiles + groups - 1) / groups);
+            w.GZ = (int)((tiles + per - 1) / per);
+            return w;
+        }
+    }
     if (g.C < 48 && J <= 576 && !(tune && tune[0] == 't')) {
         const int nb = J <= 160 ? 5 : (J <= 320 ? 10 : 18);
         if (10 * J >= 7 * 32 * nb) {
@@ -517,6 +535,18 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
     const bool veca = (OC % 4 == 0) && aligned16(dY);
     const bool vecb = (C % 4 == 0) && aligned16(X);
     hipStream_t st = (hipStream_t)stream;
+    if (w.patch == 4) {
+        StripWgradParams Q{};
+        Q.X = X; Q.dY = dY; Q.part = part;
+        Q.N = N; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = padding;
+        Q.nBands = (g.OW + 15) / 16;
+        Q.nRowTiles = (g.OH + 3) / 4;
+        Q.tiles = N * Q.nBands * Q.nRowTiles;
+        Q.tilesPerBlock = (Q.tiles + w.GZ - 1) / w.GZ;
+        const size_t lds = strip_wgrad_lds_bytes<7, 7, 3, 2>();
+        if (veca) return launch(strip_wgrad<7, 7, 3, 2, true>, Q, w.GZ, lds, st, kStripThreads);
+        return launch(strip_wgrad<7, 7, 3, 2, false>, Q, w.GZ, lds, st, kStripThreads);
+    }
     if (w.patch) {
         PatchGemmParams Q{};
         Q.X = X; Q.dY = dY; Q.Out = part;

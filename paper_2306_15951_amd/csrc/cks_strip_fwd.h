@@ -42,7 +42,7 @@ constexpr int kStripThreads = 512;
 
 template <int FH, int FW, int IC, int S>
 struct StripGeo {
-    static constexpr int TH = 4, TW = 16;
+    static constexpr int TH = 4, TW = 16, IC_ = IC, S_ = S;
     static constexpr int L = FW * IC, J = FH * L, STEPS = (J + 1) / 2;
     static constexpr int SR = (TH - 1) * S + FH;              // strip rows
     static constexpr int SWF = ((TW - 1) * S + FW) * IC;      // strip floats per row
@@ -51,6 +51,58 @@ struct StripGeo {
     static constexpr int LDW = (2 * STEPS) | 1;               // filter row pitch, odd: conflict-free column reads
     static constexpr int PASSES = (SWF + 63) / 64;
     static constexpr size_t lds_bytes() { return (size_t)(64 * LDW + 2 * STRIP) * sizeof(float); }
+};
+
+// Staging of a tile's input strip by four waves: wave pw takes strip rows pw, pw+4, ..., lane l the
+// floats l, l+64, ... of a row.  The image is one raw buffer, the row a scalar offset; floats that
+// lie outside the row (left/right padding) carry an offset beyond the buffer and read as zero,
+// rows outside the image are not read and staged as zeros.
+template <class G>
+struct StripStager {
+    static constexpr int RROWS = (G::SR + 3) / 4;
+    static constexpr int kBeyond = (int)0x80000000u;
+    float v[RROWS][G::PASSES];
+    int voff[G::PASSES];
+    int band = -1;
+
+    // tile = (image n, band c of 16 output columns, row tile t of 4 output rows)
+    __device__ __forceinline__ void fetch(const float *X, int n, int c, int t, int pw, int lane, int IH, int IW, int p)
+    {
+        const int rowFloats = IW * G::IC_;
+        if (c != band) {   // uniform: where this band's strip floats lie in an image row
+            band = c;
+            const int x0 = (c * 16 * G::S_ - p) * G::IC_;
+#pragma unroll
+            for (int q = 0; q < G::PASSES; ++q) {
+                const int x = lane + 64 * q;
+                voff[q] = (x < G::SWF && x0 + x >= 0 && x0 + x < rowFloats) ? (x0 + x) * 4 : kBeyond;
+            }
+        }
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(X) + (long)n * IH * rowFloats, 0, IH * rowFloats * 4, 0x00020000);
+        const int ih0 = 4 * t * G::S_ - p;
+#pragma unroll
+        for (int j = 0; j < RROWS; ++j) {
+            const int ih = ih0 + pw + 4 * j;
+            const bool in = pw + 4 * j < G::SR && ih >= 0 && ih < IH;   // uniform
+#pragma unroll
+            for (int q = 0; q < G::PASSES; ++q)
+                v[j][q] = in ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], ih * rowFloats * 4, 0)) : 0.f;
+        }
+    }
+    // strip: start of the strip buffer to fill
+    __device__ __forceinline__ void stage(float *strip, int pw, int lane) const
+    {
+        float *dst = strip + pw * G::RP + lane;
+#pragma unroll
+        for (int j = 0; j < RROWS; ++j) {
+            if (pw + 4 * j < G::SR) {
+#pragma unroll
+                for (int q = 0; q < G::PASSES; ++q)
+                    if (lane + 64 * q < G::SWF) dst[4 * j * G::RP + 64 * q] = v[j][q];
+            }
+        }
+    }
 };
 
 // The K loop, unrolled in groups of kStripGroup steps: the LDS reads of group g+1 are issued, then
@@ -93,7 +145,7 @@ template <int FH, int FW, int IC, int S>
 __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams P)
 {
     using G = StripGeo<FH, FW, IC, S>;
-    constexpr int L = G::L, J = G::J, STEPS = G::STEPS, SR = G::SR, SWF = G::SWF, RP = G::RP, STRIP = G::STRIP, LDW = G::LDW;
+    constexpr int L = G::L, J = G::J, RP = G::RP, STRIP = G::STRIP, LDW = G::LDW;
     constexpr int kBeyond = (int)0x80000000u;   // an offset outside every descriptor used here
     extern __shared__ __align__(16) float smem[];
     float *Ws = smem;                 // [64][LDW]
@@ -113,7 +165,6 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
         if (oc0 + r < P.OC) Ws[r * LDW + j] = P.W[(long)(oc0 + r) * J + j];
     }
 
-    const int rowFloats = P.IW * IC;
     // tile index -> (image, band, row tile); row tiles fastest, so a workgroup runs down a band
     auto decode = [&](int tile, int &n, int &c, int &t) {
         t = tile % P.nRowTiles;
@@ -124,55 +175,26 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
 
     if (wave >= 4) {
         // ---------------------------------------------------------------- staging waves
-        // wave pw takes strip rows pw, pw+4, ...; lane l the floats l, l+64, ... of a row
         const int pw = wave - 4;
-        constexpr int RROWS = (SR + 3) / 4;
-        float *dst = Ss + pw * RP + lane;
-        float v[RROWS][G::PASSES];
-        int voff[G::PASSES];
-        int band = -1;
+        StripStager<G> stager;
         auto fetch = [&](int tile) {
             if (tile >= tile_end) return;   // uniform
             int n, c, t;
             decode(tile, n, c, t);
-            if (c != band) {   // uniform: where this band's strip floats lie in an image row
-                band = c;
-                const int x0 = (c * 16 * S - P.p) * IC;
-#pragma unroll
-                for (int q = 0; q < G::PASSES; ++q) {
-                    const int x = lane + 64 * q;
-                    voff[q] = (x < SWF && x0 + x >= 0 && x0 + x < rowFloats) ? (x0 + x) * 4 : kBeyond;
-                }
-            }
-            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<float *>(P.X) + (long)n * P.IH * rowFloats, 0, P.IH * rowFloats * 4, 0x00020000);
-            const int ih0 = 4 * t * S - P.p;
-#pragma unroll
-            for (int j = 0; j < RROWS; ++j) {
-                const int ih = ih0 + pw + 4 * j;
-                const bool in = pw + 4 * j < SR && ih >= 0 && ih < P.IH;   // uniform
-#pragma unroll
-                for (int q = 0; q < G::PASSES; ++q)
-                    v[j][q] = in ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], ih * rowFloats * 4, 0)) : 0.f;
-            }
+            stager.fetch(P.X, n, c, t, pw, lane, P.IH, P.IW, P.p);
         };
         auto stage = [&](int tile, int buf) {
-            if (tile >= tile_end) return;
-#pragma unroll
-            for (int j = 0; j < RROWS; ++j) {
-                if (pw + 4 * j < SR) {
-#pragma unroll
-                    for (int q = 0; q < G::PASSES; ++q)
-                        if (lane + 64 * q < SWF) dst[buf * STRIP + 4 * j * RP + 64 * q] = v[j][q];
-                }
-            }
+            if (tile < tile_end) stager.stage(Ss + buf * STRIP, pw, lane);
         };
         fetch(tile_beg);
         stage(tile_beg, 0);
+        fetch(tile_beg + 1);
         __syncthreads();
+        // the loads of tile t+2 are issued as soon as the registers of tile t+1 have gone to LDS: they
+        // have a whole tile's time to arrive
         for (int tile = tile_beg; tile < tile_end; ++tile) {
-            fetch(tile + 1);
             stage(tile + 1, (tile + 1 - tile_beg) & 1);
+            fetch(tile + 2);
             __syncthreads();
         }
         return;
@@ -206,7 +228,7 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
         floatx16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        float av[STEPS], bv[STEPS];
+        float av[G::STEPS], bv[G::STEPS];
         StripKLoop<G, 0>::run(av, bv, acc, a_same + sb, a_wrap + sb, a_last + sb, b_ptr);
 
         int n, c, tt;
