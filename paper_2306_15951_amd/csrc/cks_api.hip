@@ -507,7 +507,7 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
         const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
         const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2 && OC == 64;
         if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, blocks, lds, st, kScatterThreads);
-        else if (stem) rc = launch(scatter_deconv<10, true>, S.P, blocks, lds, st, kScatterThreads);
+        else if (stem) rc = launch(scatter_deconv<10, true>, S.P, blocks, lds, st, kScatterStemThreads);
         else rc = launch(scatter_deconv<10, false>, S.P, blocks, lds, st, kScatterThreads);
         if (rc != CKS_OK || S.headBytes == 0) return rc;
         BandHeadParams B{};

@@ -49,7 +49,8 @@ struct ScatterDeconvParams {
     int KP;             // OC rounded up to 16
 };
 
-constexpr int kScatterThreads = 512;
+constexpr int kScatterThreads = 512;       // 4 MFMA waves + 4 staging waves
+constexpr int kScatterStemThreads = 768;   // 8 MFMA waves (two per dY row) + 4 staging waves
 constexpr int kScatterLDK = 68;    // K <= 64, +4 keeps 16-row fragments conflict free
 constexpr int kScatterPP = 20;     // scratch floats per column: 16 pixels + 4 (bank skew, keeps float4 alignment)
 constexpr int kScatterRP = 128;    // floats per Q row
@@ -59,12 +60,83 @@ inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
     return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + ((size_t)slots * FH + 1) * kScatterRP) * sizeof(float);
 }
 
+// One pass of a stem MFMA wave (OC = 64: four K groups of 16): NBH column blocks of P for its dY
+// row, and step 1 for NFH filter rows of the row it computed in the previous pass (that P is still
+// in the wave's scratch, which is overwritten only at the end of this pass).  The filter fragments
+// of K group u+1 are requested before the MFMAs of group u are issued and one filter row's gather
+// reads ride along with each group; the few adds fall between MFMAs.  The order is pinned (the
+// compiler would sink every read to its use), and never more than 15 LDS reads are outstanding at
+// a wait, which is all the counter can express.
+template <int NBH, int NFH, bool MFMAS>
+__device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const float *Bp, const float *const (&gat)[2][kScatterMaxTB],
+                                                  int fhStride, float *qrow, float *Pst)
+{
+    constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
+    float g[NFH][2][MAXTB];
+    if constexpr (MFMAS) {
+        floatx4 acc[NBH];
+#pragma unroll
+        for (int b = 0; b < NBH; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float4 wc[NBH], wn[NBH];
+#pragma unroll
+        for (int b = 0; b < NBH; ++b) wc[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK);
+        __builtin_amdgcn_sched_group_barrier(0x100, NBH, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u < 3) {
+#pragma unroll
+                for (int b = 0; b < NBH; ++b) wn[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * (u + 1));
+            }
+            if (u < NFH) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int tb = 0; tb < MAXTB; ++tb) g[u][q][tb] = gat[q][tb][u * fhStride];
+            }
+#pragma unroll
+            for (int b = 0; b < NBH; ++b) {
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, wc[b].x, acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, wc[b].y, acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, wc[b].z, acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, wc[b].w, acc[b], 0, 0, 0);
+            }
+            if (u < 3) __builtin_amdgcn_sched_group_barrier(0x100, NBH, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+            if (u < NFH) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * NBH - 8, 0);
+#pragma unroll
+            for (int b = 0; b < NBH; ++b) wc[b] = wn[b];
+        }
+#pragma unroll
+        for (int fh = 0; fh < NFH; ++fh)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+#pragma unroll
+        for (int b = 0; b < NBH; ++b)
+            *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+    } else {
+#pragma unroll
+        for (int fh = 0; fh < NFH; ++fh)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int tb = 0; tb < MAXTB; ++tb) g[fh][q][tb] = gat[q][tb][fh * fhStride];
+#pragma unroll
+        for (int fh = 0; fh < NFH; ++fh)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+    }
+}
+
 // NB: 16-column blocks of the GEMM (J <= 16 NB).  STEM: the geometry is the
 // 7x7 / stride 2 / 3-channel stem, known at compile time, so that every LDS
 // access of the composing steps is "lane constant + immediate".
 template <int NB, bool STEM>
-__global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterDeconvParams P)
+__global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) scatter_deconv(const ScatterDeconvParams P)
 {
+    constexpr int THREADS = STEM ? kScatterStemThreads : kScatterThreads, NCW = THREADS / 64 - 4;   // MFMA waves
     constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
     constexpr int kBeyond = (int)0x80000000u;   // an offset outside every descriptor used here
     const int FH = STEM ? 7 : P.FH, FW = STEM ? 7 : P.FW, IC = STEM ? 3 : P.IC, S = STEM ? 2 : P.s;
@@ -83,20 +155,22 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     const int rows4s = 4 * S;
 
     const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + (SLOTS * FH + 1) * RP;
-    for (int i = tid; i < ldsFloats; i += kScatterThreads) smem[i] = 0.f;
+    for (int i = tid; i < ldsFloats; i += THREADS) smem[i] = 0.f;
     __syncthreads();
-    for (int i = tid; i < P.OC * J; i += kScatterThreads) {
+    for (int i = tid; i < P.OC * J; i += THREADS) {
         const int oc = i / J, j = i - oc * J;
-        Bs[j * LDK + oc] = P.W[i];
+        // stem: filter rows 0-3 are columns 0..83, rows 4-6 start at column 96 (one MFMA wave each)
+        const int col = STEM && j >= 4 * L ? j + (96 - 4 * L) : j;
+        Bs[col * LDK + oc] = P.W[i];
     }
     __syncthreads();
 
-    if (wave >= 4) {
+    if (wave >= NCW) {
         // ------------------------------------------------------------ staging waves: step 2 and the stores
         // These waves issue few instructions, each of which would otherwise queue behind the MFMA
         // wave of the same SIMD.
         __builtin_amdgcn_s_setprio(3);
-        const int pw = wave - 4;
+        const int pw = wave - NCW;
         // Q float x of this band is dX float (ow0*s - p)*IC + x of its image row.  The image (and this
         // band's side buffer) is one raw buffer, the row a scalar offset; lanes outside the row or not
         // written by this band carry an offset beyond it.
@@ -155,8 +229,12 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     // ---------------------------------------------------------------- MFMA waves: wave w owns dY row 4i + w of step i
     // 16x16x4 MFMA: lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16];
     // result register r holds D[m = 4*(l/16) + r][n = l%16].
+    // Stem: waves 0-3 take filter rows 0-3 (column blocks 0-5) of dY rows 0-3 of the step, waves 4-7
+    // filter rows 4-6 (blocks 6-9): each SIMD then hosts two MFMA waves that fill each other's stalls.
     const int lm = lane & 15, lk = lane >> 4;
     const int KU = P.KP >> 4;
+    const int wrow = STEM ? (wave & 3) : wave, half = STEM ? (wave >> 2) : 0;
+    const int colBase = half ? 96 : 0, fhBase = half ? 4 : 0;
     // A straight from global: pixel lm, channels 16u + 4lk .. +3 (channels past OC are out of range)
     int a_voff[4];
 #pragma unroll
@@ -164,7 +242,7 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     const int a_bytes = min(16, P.OW - ow0) * P.OC * 4;
     float4 areg[4];
     auto fetch = [&](int i) {
-        const int oh = 4 * i + wave;
+        const int oh = 4 * i + wrow;
         const long off = (((long)n * P.OH + min(oh, P.OH - 1)) * P.OW + ow0) * P.OC;
         const __amdgpu_buffer_rsrc_t rs =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + off), 0, oh < P.OH ? a_bytes : 0, 0x00020000);
@@ -173,7 +251,7 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
             areg[u] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff[u], 0, 0));
     };
     // step 1, lane constants: ring float x = lane + 64q is pixel column pwx = x / IC (= v*s + b), channel ic
-    float *Pw = Ps + wave * NB * 16 * PP;
+    float *Pw = Ps + (wrow * NB * 16 + colBase) * PP;   // this wave's columns of its row's scratch
     const float *gat[2][MAXTB];
     const int touched = (15 * S + FW) * IC;
 #pragma unroll
@@ -190,85 +268,26 @@ __global__ void __launch_bounds__(kScatterThreads) scatter_deconv(const ScatterD
     }
     const int fhStride = L * PP;
     float *Pst = Pw + lm * PP + 4 * lk;   // + b*16*PP: P[pixels 4lk..4lk+3][column 16b + lm]
-    const float *Bp = Bs + lm * LDK + 4 * lk;
+    const float *Bp = Bs + (colBase + lm) * LDK + 4 * lk;
 
     fetch(0);
     if constexpr (STEM) {
-        // OC = 64: four K groups.  The filter fragments of group u+1 are requested before the MFMAs
-        // of group u are issued, and step 1 of the previous dY row (its P is still in the scratch,
-        // which is overwritten only after this row's MFMAs) rides along: its LDS reads join the
-        // fragment reads, its few adds fall between MFMAs.  The order is pinned; the compiler would
-        // otherwise sink every read to its use.
         for (int i = 0; i <= P.nFlush + 1; ++i) {
-            // Q row of dY row 4(i-1) + wave; in the first pass the scratch is still all zero and the
+            // Q rows of dY row 4(i-1) + wrow; in the first pass the scratch is still all zero and the
             // zero row receives zeros
-            float *qrow = (i > 0 ? Qs + (((4 * (i - 1) + wave) % SLOTS) * 7) * RP : Qs + SLOTS * 7 * RP) + lane;
+            float *qrow = (i > 0 ? Qs + (((4 * (i - 1) + wrow) % SLOTS) * 7 + fhBase) * RP : Qs + SLOTS * 7 * RP) + lane;
             if (i < P.nTiles) {   // uniform
-                floatx4 acc[NB];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
                 float4 a[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) a[u] = areg[u];
                 if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
-                float4 wc[NB], wn[NB];
-                float g[7][2][MAXTB];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) wc[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK);
-                __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (u < 3) {
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) wn[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * (u + 1));
-                    }
-                    const int fhA = 2 * u, fhB = u < 3 ? 2 * u + 2 : 7;   // filter rows gathered alongside group u
-#pragma unroll
-                    for (int fh = fhA; fh < fhB; ++fh)
-#pragma unroll
-                        for (int q = 0; q < 2; ++q)
-#pragma unroll
-                            for (int tb = 0; tb < MAXTB; ++tb) g[fh][q][tb] = gat[q][tb][fh * fhStride];
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, wc[b].x, acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, wc[b].y, acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, wc[b].z, acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, wc[b].w, acc[b], 0, 0, 0);
-                    }
-                    // at most 15 LDS reads can be counted as outstanding: the fragment reads go first, the
-                    // gather reads follow in two batches once the group's MFMAs are under way
-                    if (u < 3) __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-                    if (u < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * NB - 16, 0);
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) wc[b] = wn[b];
-                }
-#pragma unroll
-                for (int fh = 0; fh < 7; ++fh)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-                        qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+                if (half == 0) scatter_stem_pass<6, 4, true>(a, Bp, gat, fhStride, qrow, Pst);
+                else scatter_stem_pass<4, 3, true>(a, Bp, gat, fhStride, qrow, Pst);
             } else if (i == P.nTiles) {
                 // the last dY rows: step 1 on its own
-                float g[7][2][MAXTB];
-#pragma unroll
-                for (int fh = 0; fh < 7; ++fh)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-#pragma unroll
-                        for (int tb = 0; tb < MAXTB; ++tb) g[fh][q][tb] = gat[q][tb][fh * fhStride];
-#pragma unroll
-                for (int fh = 0; fh < 7; ++fh)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-                        qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+                float4 a[4];
+                if (half == 0) scatter_stem_pass<6, 4, false>(a, Bp, gat, fhStride, qrow, Pst);
+                else scatter_stem_pass<4, 3, false>(a, Bp, gat, fhStride, qrow, Pst);
             }
             __syncthreads();
         }
