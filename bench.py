@@ -171,6 +171,8 @@ def main():
     ap.add_argument("--config", default="cfg1")
     ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (extra JSON field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only a plain 1 GiB -> 1 GiB streaming kernel (calibrates the HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -180,6 +182,17 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if a.copy_probe:
+        # out = in * 1: every launch reads 1 GiB and writes 1 GiB, nothing else
+        n = 1 << 28
+        src = torch.ones(n, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": "torch.mul(src, 1.0, out=dst), float32", "bytes_read_per_launch": 4 * n,
+                          "bytes_written_per_launch": 4 * n, "launches": 5}))
+        return
     L = synth.LAYERS[a.config]
     B, r = bench_layer(L, a.steps, a.warmup)
 
