@@ -133,6 +133,19 @@ MID = [
     ("patch_ic3_pad_ge_filter", 6, 3, 6, 7, 8, 7, 7, 3, 7),
     ("gray_1ch", 5, 1, 10, 11, 70, 3, 3, 1, 1),
     ("ic7_5x5", 3, 7, 9, 9, 65, 5, 5, 1, 2),
+    # image stems: 7x7/s2 on 3 channels has kernels of its own (input strip in LDS; tap-stationary input
+    # gradient with 64 output channels), other few-channel layers take the generic variants of those
+    ("stem_oc64_ragged", 3, 3, 40, 37, 64, 7, 7, 2, 3),
+    ("stem_oc70", 2, 3, 23, 50, 70, 7, 7, 2, 3),
+    ("stem_pad0", 2, 3, 21, 33, 8, 7, 7, 2, 0),
+    ("stem_pad5_tiny", 3, 3, 7, 9, 12, 7, 7, 2, 5),
+    ("stem_remainder_rows", 2, 3, 32, 31, 64, 7, 7, 2, 3),
+    ("stem_single_pixel_rows", 1, 3, 9, 130, 64, 7, 7, 2, 3),
+    ("rgb_3x3", 6, 3, 20, 21, 16, 3, 3, 1, 1),
+    ("rgb_5x5_s2", 4, 3, 19, 40, 32, 5, 5, 2, 2),
+    ("rgb_4x4_s3", 3, 3, 17, 35, 8, 4, 4, 3, 1),
+    ("rgb_wide", 2, 3, 9, 70, 4, 3, 3, 1, 1),
+    ("two_ch_6x6_s2", 3, 2, 15, 18, 60, 6, 6, 2, 2),
 ]
 
 
@@ -213,13 +226,22 @@ def test_stage_entry_points(cks, oracle):
     assert_exact(dX.cpu().numpy(), oracle.deconv(dY, W, L.IH, L.IW, 2, 1), "presplit")
 
 
-def test_no_write_outside_outputs_and_unaligned_pointers(cks, oracle):
+GUARD = [
+    ("guards", 37, 8, 7, 9, 12, 3, 3, 2, 1),
+    ("guards_stem", 5, 3, 23, 26, 64, 7, 7, 2, 3),
+    ("guards_rgb", 7, 3, 10, 19, 12, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("guard_geo", GUARD, ids=[g[0] for g in GUARD])
+def test_no_write_outside_outputs_and_unaligned_pointers(cks, oracle, guard_geo):
     """Outputs, inputs and workspaces sit inside guard bands; offsets of one
     float make every pointer 4-byte aligned only (scalar load path)."""
     import torch
     from paper_2306_15951_amd import synth
 
-    L = synth.Layer("guards", 37, 8, 7, 9, 12, 3, 3, 2, 1)
+    L = synth.Layer(*guard_geo)
+    print("geometry", guard_geo, flush=True)
     g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
     X, W, dY = synth.make_inputs(L, "int", 2)
     OH, OW = cks.cks_out_dims(L.IH, L.IW, L.FH, L.FW, L.stride, L.padding)
@@ -271,6 +293,26 @@ def test_wgrad_is_reproducible_bit_for_bit(cks):
         torch.cuda.synchronize()
         outs.append(dW.cpu().numpy().view(np.uint32))
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_stem_deconv_is_reproducible_bit_for_bit(cks):
+    """The few-channel input gradient composes its sums in a fixed order (no atomics)."""
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer("stem_repro", 8, 3, 112, 112, 64, 7, 7, 2, 3)
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+    X, W, dY = synth.make_inputs(L, "normal", 5)
+    ws = torch.empty(max(cks.cks_deconv2d_workspace(*g) // 4, 1), device="cuda")
+    outs = []
+    for _ in range(3):
+        dX = nan_like(X.shape)
+        ws.fill_(float("nan"))
+        cks.cks_deconv2d(dev(dY), dev(W), dX, L.stride, L.padding, ws)
+        torch.cuda.synchronize()
+        outs.append(dX.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    assert np.isfinite(outs[0]).all()
 
 
 def test_errors_on_device(cks):
