@@ -181,6 +181,51 @@ int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int 
 
 constexpr int kStripWgradGroups = kCUs;   // strip_wgrad: one workgroup (= one segment) per compute unit
 
+// Few-channel geometries the strip kernels are instantiated for: 1 = 7x7 / stride 2 / 3 channels (ImageNet
+// stems), 2 = 3x3 / stride 1 / 3 channels, 3 = 3x3 / stride 2 / 3 channels (small-image stems); 0 = none.
+inline int strip_geometry(int FH, int FW, int C, int s)
+{
+    if (C != 3 || FH != FW) return 0;
+    if (FH == 7 && s == 2) return 1;
+    if (FH == 3 && s == 1) return 2;
+    if (FH == 3 && s == 2) return 3;
+    return 0;
+}
+
+template <int FH, int FW, int IC, int S>
+int launch_strip_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_t st)
+{
+    using SG = StripGeo<FH, FW, IC, S>;
+    StripFwdParams Q{};
+    Q.X = X; Q.W = Wt; Q.Y = Y;
+    Q.N = g.N; Q.IH = g.H; Q.IW = g.W; Q.OC = g.OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = g.p;
+    Q.nBands = (g.OW + 15) / 16;
+    Q.nRowTiles = (g.OH + 3) / 4;
+    Q.nT = (g.OC + 63) / 64;
+    const long long tiles = (long long)g.N * Q.nBands * Q.nRowTiles;
+    if (!fits_i31(tiles * Q.nT)) return CKS_ERR_SHAPE;
+    Q.tiles = (int)tiles;
+    const int groups = Q.tiles < 2 * kCUs ? Q.tiles : 2 * kCUs;   // two workgroups per compute unit
+    Q.tilesPerBlock = (Q.tiles + groups - 1) / groups;
+    const int blocks = ((Q.tiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
+    return launch(strip_fwd<FH, FW, IC, S>, Q, blocks, SG::lds_bytes(), st, kStripThreads);
+}
+
+template <int FH, int FW, int IC, int S>
+int launch_strip_wgrad(const Geo &g, int GZ, const float *X, const float *dY, float *part, bool veca, hipStream_t st)
+{
+    StripWgradParams Q{};
+    Q.X = X; Q.dY = dY; Q.part = part;
+    Q.N = g.N; Q.IH = g.H; Q.IW = g.W; Q.OC = g.OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = g.p;
+    Q.nBands = (g.OW + 15) / 16;
+    Q.nRowTiles = (g.OH + 3) / 4;
+    Q.tiles = g.N * Q.nBands * Q.nRowTiles;
+    Q.tilesPerBlock = (Q.tiles + GZ - 1) / GZ;
+    const size_t lds = strip_wgrad_lds_bytes<FH, FW, IC, S>();
+    if (veca) return launch(strip_wgrad<FH, FW, IC, S, true>, Q, GZ, lds, st, kStripThreads);
+    return launch(strip_wgrad<FH, FW, IC, S, false>, Q, GZ, lds, st, kStripThreads);
+}
+
 struct WgradPlan {
     int patch;    // 0: one tile per filter tap (pixel_gemm); 1..3: all taps in one tile (patch_gemm); 4: strip_wgrad
     int variant, bm, bn, mTiles, nTiles, GZ;
@@ -208,8 +253,8 @@ WgradPlan plan_wgrad(const Geo &g)
     // Put the whole filter patch (J = FH*FW*IC columns) into one tile if it
     // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
     const long long J = (long long)g.FH * g.FW * g.C;
-    // the 7x7 / stride 2 / 3-channel stem: input strip in LDS (strip_wgrad), one segment per workgroup
-    if (g.FH == 7 && g.FW == 7 && g.C == 3 && g.s == 2 && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
+    // image stems: input strip in LDS (strip_wgrad), one segment per workgroup
+    if (strip_geometry(g.FH, g.FW, g.C, g.s) && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
         !tune && !getenv("CKS_TUNE_NO_STRIP_WGRAD")) {
         const long long tiles = (long long)g.N * ((g.OW + 15) / 16) * ((g.OH + 3) / 4);
         if (fits_i31(tiles)) {
@@ -423,22 +468,13 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
     // Image stems (very few input channels): one GEMM over all pixels with the
     // whole filter patch as contraction axis and the filter resident in LDS.
     const int KP = (FH * FW * C + 15) / 16 * 16;
-    // the 7x7 / stride 2 / 3-channel stem: input strip in LDS, addressing known at compile time
-    if (FH == 7 && FW == 7 && C == 3 && stride == 2 && (long long)H * W * C * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
-        using SG = StripGeo<7, 7, 3, 2>;
-        StripFwdParams Q{};
-        Q.X = X; Q.W = Wt; Q.Y = Y;
-        Q.N = N; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = padding;
-        Q.nBands = (g.OW + 15) / 16;
-        Q.nRowTiles = (g.OH + 3) / 4;
-        Q.nT = (OC + 63) / 64;
-        const long long tiles = (long long)N * Q.nBands * Q.nRowTiles;
-        if (fits_i31(tiles * Q.nT)) {
-            Q.tiles = (int)tiles;
-            const int groups = Q.tiles < 2 * kCUs ? Q.tiles : 2 * kCUs;   // two workgroups per compute unit
-            Q.tilesPerBlock = (Q.tiles + groups - 1) / groups;
-            const int blocks = ((Q.tiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
-            return launch(strip_fwd<7, 7, 3, 2>, Q, blocks, SG::lds_bytes(), (hipStream_t)stream, kStripThreads);
+    // image stems: input strip in LDS, addressing known at compile time
+    if ((long long)H * W * C * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
+        switch (strip_geometry(FH, FW, C, stride)) {
+            case 1: return launch_strip_fwd<7, 7, 3, 2>(g, X, Wt, Y, (hipStream_t)stream);
+            case 2: return launch_strip_fwd<3, 3, 3, 1>(g, X, Wt, Y, (hipStream_t)stream);
+            case 3: return launch_strip_fwd<3, 3, 3, 2>(g, X, Wt, Y, (hipStream_t)stream);
+            default: break;
         }
     }
     if (C < 8 && KP <= kPatchFwdMaxKP && (long long)N * H * W * C * 4 < (1LL << 31) &&
@@ -536,16 +572,12 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
     const bool vecb = (C % 4 == 0) && aligned16(X);
     hipStream_t st = (hipStream_t)stream;
     if (w.patch == 4) {
-        StripWgradParams Q{};
-        Q.X = X; Q.dY = dY; Q.part = part;
-        Q.N = N; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = padding;
-        Q.nBands = (g.OW + 15) / 16;
-        Q.nRowTiles = (g.OH + 3) / 4;
-        Q.tiles = N * Q.nBands * Q.nRowTiles;
-        Q.tilesPerBlock = (Q.tiles + w.GZ - 1) / w.GZ;
-        const size_t lds = strip_wgrad_lds_bytes<7, 7, 3, 2>();
-        if (veca) return launch(strip_wgrad<7, 7, 3, 2, true>, Q, w.GZ, lds, st, kStripThreads);
-        return launch(strip_wgrad<7, 7, 3, 2, false>, Q, w.GZ, lds, st, kStripThreads);
+        switch (strip_geometry(FH, FW, C, stride)) {
+            case 1: return launch_strip_wgrad<7, 7, 3, 2>(g, w.GZ, X, dY, part, veca, st);
+            case 2: return launch_strip_wgrad<3, 3, 3, 1>(g, w.GZ, X, dY, part, veca, st);
+            case 3: return launch_strip_wgrad<3, 3, 3, 2>(g, w.GZ, X, dY, part, veca, st);
+            default: return CKS_ERR_UNSUPPORTED;
+        }
     }
     if (w.patch) {
         PatchGemmParams Q{};
