@@ -163,6 +163,97 @@ def bench_layer(L, steps, warmup, with_kernels=True):
     return B, out
 
 
+# Invented stand-ins for the paper's first experiment (its 16 shapes per operator are not disclosed):
+# two filter sets, eight shapes each with shrinking maps and growing channels, and a stride series.
+SWEEP = (
+    [("3x3p1_%d" % i, n, c, hw, hw, c, 3, 3, 1, 1) for i, (n, c, hw) in enumerate(
+        [(64, 64, 64), (128, 64, 32), (64, 128, 32), (128, 128, 16), (64, 256, 16), (128, 256, 8), (128, 512, 8), (256, 512, 4)])] +
+    [("5x5p2_%d" % i, n, c, hw, hw, c, 5, 5, 1, 2) for i, (n, c, hw) in enumerate(
+        [(64, 64, 64), (128, 64, 32), (64, 128, 32), (128, 128, 16), (64, 256, 16), (128, 256, 8), (128, 512, 8), (256, 512, 4)])] +
+    [("5x5p2_s%d" % st, 64, 128, 32, 32, 128, 5, 5, st, 2) for st in (2, 3, 4)]
+)
+
+
+def warm_gpu():
+    """Half a second of the cfg1 step, so that short timings that follow run at the sustained clock."""
+    from paper_2306_15951_amd import synth
+
+    B = LayerBench(synth.LAYERS["cfg1"])
+    B.time_ms(B.step, 1500, 10)
+
+
+def sweep(steps, warmup):
+    """Useful TFLOP/s of the three operators over the SWEEP shapes."""
+    import torch
+    from paper_2306_15951_amd import synth
+
+    rows = {}
+    for geo in SWEEP:
+        B = LayerBench(synth.Layer(*geo))
+        r = {}
+        for name, fn in (("conv2d_fwd", B.fwd), ("deconv2d", B.deconv), ("dilated_conv2d_wgrad", B.wgrad)):
+            ms = B.time_ms(fn, steps, warmup)
+            r[name] = {"ms": ms, "pct_fp32_mfma_peak": 100 * B.useful_flops / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS}
+        rows[geo[0]] = {"geometry": geo[1:], "useful_gflop": B.useful_flops / 1e9, "operators": r}
+        del B
+        torch.cuda.empty_cache()
+    return rows
+
+
+def ablation(L, steps, warmup):
+    """Skipping zeros against multiplying them, with the same kernels: each operator is also run in
+    its textbook form on tensors with the zeros written out (padding border; stride-inserted zeros
+    + rotated filter; dilated gradient), through cks_conv2d_fwd with padding 0."""
+    import torch
+    import torch.nn.functional as F
+
+    B = LayerBench(L)
+    cks, s, p = B.cks, L.stride, L.padding
+    OH, OW = cks.cks_out_dims(L.IH, L.IW, L.FH, L.FW, s, p)
+    out = {"useful_gflop": B.useful_flops / 1e9}
+
+    def timed(fn):
+        return min(B.time_ms(fn, steps, warmup), B.time_ms(fn, steps, 5))
+
+    def close(a, b):
+        return float((a - b).abs().max() / max(float(b.abs().max()), 1e-30))
+
+    # ConvV2 | padded input, padding 0
+    Xp = F.pad(B.X, (0, 0, p, p, p, p)).contiguous()
+    Y2 = torch.empty_like(B.Y)
+    B.fwd(); cks.cks_conv2d_fwd(Xp, B.W, Y2, s, 0)
+    out["conv2d_fwd"] = {"skip_ms": timed(B.fwd), "dense_ms": timed(lambda: cks.cks_conv2d_fwd(Xp, B.W, Y2, s, 0)),
+                         "max_rel_diff": close(Y2, B.Y)}
+    # KS-deconv | zero-inserted gradient on a zero canvas, rotated filter, unit stride
+    Z = torch.zeros((L.N, L.IH + L.FH - 1, L.IW + L.FW - 1, L.OC), device=B.X.device)
+    o = (L.FH - 1 - p, L.FW - 1 - p)
+    hs, ws = (OH - 1) * s + 1, (OW - 1) * s + 1
+    ih = torch.arange(0, hs, s, device=B.X.device) + o[0]
+    iw = torch.arange(0, ws, s, device=B.X.device) + o[1]
+    mh, mw = (ih >= 0) & (ih < Z.shape[1]), (iw >= 0) & (iw < Z.shape[2])
+    Z[:, ih[mh][:, None], iw[mw][None, :], :] = B.dY[:, mh][:, :, mw]
+    Wr = B.W.flip(1, 2).permute(3, 1, 2, 0).contiguous()      # [IC, FH, FW, OC]
+    dX2 = torch.empty_like(B.dX)
+    B.deconv(); cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0)
+    out["deconv2d"] = {"skip_ms": timed(B.deconv), "dense_ms": timed(lambda: cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0)),
+                       "max_rel_diff": close(dX2, B.dX)}
+    # Sk-dilated | dilated gradient as the filter of a unit-stride convolution over the padded input
+    # (image axis and channel axis change places: the contraction runs over n)
+    D = torch.zeros((L.N, hs, ws, L.OC), device=B.X.device)
+    D[:, ::s, ::s, :] = B.dY
+    need_h, need_w = hs + L.FH - 1, ws + L.FW - 1                    # padded rows the FH x FW output uses
+    Xq = Xp[:, :need_h, :need_w, :].permute(3, 1, 2, 0).contiguous()   # [IC, rows, cols, N]
+    Dq = D.permute(3, 1, 2, 0).contiguous()                            # [OC, hs, ws, N]
+    dWq = torch.empty((L.IC, L.FH, L.FW, L.OC), device=B.X.device)
+    B.wgrad(); cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0)
+    out["dilated_conv2d_wgrad"] = {"skip_ms": timed(B.wgrad), "dense_ms": timed(lambda: cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0)),
+                                   "max_rel_diff": close(dWq.permute(3, 1, 2, 0), B.dW)}
+    for v in out.values():
+        if isinstance(v, dict):
+            v["speedup"] = v["dense_ms"] / v["skip_ms"]
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -171,6 +262,9 @@ def main():
     ap.add_argument("--config", default="cfg1")
     ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (extra JSON field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="only: the three operators over a sweep of invented shapes")
+    ap.add_argument("--ablation", action="store_true",
+                    help="only: zeros skipped against zeros multiplied, same kernels, on the benchmark layers")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB -> 1 GiB streaming kernel (calibrates the HBM byte counters)")
     a = ap.parse_args()
@@ -192,6 +286,19 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe": "torch.mul(src, 1.0, out=dst), float32", "bytes_read_per_launch": 4 * n,
                           "bytes_written_per_launch": 4 * n, "launches": 5}))
+        return
+    if a.sweep or a.ablation:
+        warm_gpu()
+    if a.sweep:
+        # freshly allocated buffers run slower for their first ~60 launches: long warm-up per operator
+        print(json.dumps({"sweep": sweep(max(a.steps // 2, 10), max(3 * a.warmup, 60)), "data": "synthetic, invented shapes"}))
+        return
+    if a.ablation:
+        res = {}
+        for name in ("cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4a"):
+            res[name] = ablation(synth.LAYERS[name], max(a.steps // 2, 10), max(3 * a.warmup, 60))
+            torch.cuda.empty_cache()
+        print(json.dumps({"ablation": res, "data": "synthetic"}))
         return
     L = synth.LAYERS[a.config]
     B, r = bench_layer(L, a.steps, a.warmup)
@@ -224,7 +331,7 @@ def main():
                 continue
             del B
             torch.cuda.empty_cache()
-            B, rr = bench_layer(synth.LAYERS[name], max(a.steps // 4, 10), max(a.warmup // 2, 5))
+            B, rr = bench_layer(synth.LAYERS[name], max(a.steps // 4, 10), max(a.warmup, 5))
             others[name] = rr
         line["other_configs"] = others
     print(json.dumps(line))
