@@ -185,6 +185,20 @@ def test_full_size_configs_sampled(cks, oracle, name):
     check_layer(cks, oracle, L, samples=samples)
 
 
+def test_tensors_beyond_2GiB_sampled(cks, oracle):
+    """X and dX of 2.4 GB: element offsets no longer fit 31 bits of bytes, so the kernels take
+    their 64-bit addressing paths (no scalar-offset buffer loads); sampled outputs against the oracle."""
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer("beyond_2GiB", 9, 64, 1024, 1024, 16, 3, 3, 1, 1)
+    assert L.N * L.IH * L.IW * L.IC * 4 > 2 ** 31
+    print("layer", L, flush=True)
+    rng = np.random.default_rng(77)
+    shapes = ((L.N, L.IH, L.IW, L.OC), (L.N, L.IH, L.IW, L.IC), (L.OC, L.FH, L.FW, L.IC))
+    samples = tuple(structured_samples(sh, rng, 1500) for sh in shapes)
+    check_layer(cks, oracle, L, seed=9, kinds=("normal",), samples=samples)
+
+
 def test_full_size_cfg1_every_element(cks, oracle):
     """One benchmark layer compared in full, not sampled (forward and input gradient)."""
     from paper_2306_15951_amd import synth
