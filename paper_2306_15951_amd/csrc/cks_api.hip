@@ -407,7 +407,8 @@ struct ScatterPlan {
     bool ok;
     int NB;             // 16-column blocks (template parameter to use)
     ScatterDeconvParams P;
-    size_t headBytes;
+    int blocks;
+    size_t headBytes, rowheadBytes;   // side buffers in the workspace, in this order
 };
 
 static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
@@ -434,8 +435,36 @@ static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC
     P.KP = (OC + 15) / 16 * 16;
     S.NB = J <= 64 ? 4 : 10;
     if (scatter_deconv_lds_bytes(S.NB, P.slots, FH) > 160 * 1024) return S;
-    if (!fits_i31((long long)N * P.nBands)) return S;
-    S.headBytes = (size_t)N * (P.nBands - 1) * H * P.OVF * sizeof(float);
+    if (!fits_i31((long long)N * P.nBands * H) || P.OVF > kThreads) return S;   // add_band_heads indexes rows with 32 bits
+    const long long steps = (long long)N * P.nBands * P.nTiles;
+    if (!fits_i31(steps)) return S;
+    P.steps = (int)steps;
+    P.HR = FH > stride ? FH - stride : 0;
+    // One workgroup per compute unit, each with an equal run of consecutive sweep steps; a run that
+    // starts inside a band shares HR dX rows with the run before it (rowhead).  Two such row heads of
+    // neighbouring bands must not meet in a dX row (their column overlap would be added to twice at
+    // once): if they would, every workgroup gets whole bands instead.
+    P.stepsPerBlock = (int)((steps + kCUs - 1) / kCUs);
+    if (P.stepsPerBlock % P.nTiles != 0) {
+        bool clash = false;
+        int prevBand = -2, prevT0 = 0;
+        const int blocks = (P.steps + P.stepsPerBlock - 1) / P.stepsPerBlock;
+        for (int b = 1; b < blocks && !clash; ++b) {
+            const long long u0 = (long long)b * P.stepsPerBlock;
+            const int band = (int)(u0 / P.nTiles), t0 = (int)(u0 % P.nTiles);
+            if (t0 == 0) continue;
+            if (band == prevBand) clash = true;   // two heads in one band: not handled
+            if (band == prevBand + 1 && band % P.nBands != 0) {
+                const int a = prevT0 * 4 * stride, c2 = t0 * 4 * stride;
+                if (a < c2 + P.HR && c2 < a + P.HR) clash = true;
+            }
+            prevBand = band; prevT0 = t0;
+        }
+        if (clash || P.HR == 0 || P.stepsPerBlock < P.nTiles) P.stepsPerBlock = (P.stepsPerBlock + P.nTiles - 1) / P.nTiles * P.nTiles;
+    }
+    S.blocks = (P.steps + P.stepsPerBlock - 1) / P.stepsPerBlock;
+    S.headBytes = ((size_t)N * (P.nBands - 1) * H * P.OVF * sizeof(float) + 255) / 256 * 256;
+    S.rowheadBytes = P.stepsPerBlock % P.nTiles != 0 ? (size_t)S.blocks * P.HR * kScatterRP * sizeof(float) : 0;
     S.ok = true;
     return S;
 }
@@ -446,7 +475,7 @@ size_t cks_deconv2d_workspace(int N, int C, int H, int W, int OC, int FH, int FW
     if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
     const size_t split = split_bytes(C, OC, FH, FW, stride);
     const ScatterPlan S = plan_scatter(g, N, C, H, W, OC, FH, FW, stride, padding);
-    return S.ok && S.headBytes > split ? S.headBytes : split;
+    return S.ok && S.headBytes + S.rowheadBytes > split ? S.headBytes + S.rowheadBytes : split;
 }
 
 int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
@@ -547,20 +576,34 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
     if (S.ok && aligned16(dY) && aligned16(ws) && !getenv("CKS_TUNE_NO_SCATTER")) {
         hipStream_t st = (hipStream_t)stream;
         S.P.dY = dY; S.P.W = Wt; S.P.dX = dX; S.P.head = (float *)ws;
-        const int blocks = N * S.P.nBands;
+        S.P.rowhead = (float *)((char *)ws + S.headBytes);
         const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
         const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2 && OC == 64;
-        if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, blocks, lds, st, kScatterThreads);
-        else if (stem) rc = launch(scatter_deconv<10, true>, S.P, blocks, lds, st, kScatterStemThreads);
-        else rc = launch(scatter_deconv<10, false>, S.P, blocks, lds, st, kScatterThreads);
-        if (rc != CKS_OK || S.headBytes == 0) return rc;
-        BandHeadParams B{};
-        B.head = (const float *)ws; B.dX = dX;
-        B.N = N; B.IC = C; B.IH = H; B.IW = W; B.s = stride; B.p = padding; B.nBands = S.P.nBands; B.OVF = S.P.OVF;
-        B.total = (long)(S.headBytes / sizeof(float));
-        const long long hb = (B.total + kThreads - 1) / kThreads;
-        if (!fits_i31(hb)) return CKS_ERR_SHAPE;
-        return launch(add_band_heads, B, (int)hb, 0, st);
+        if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, S.blocks, lds, st, kScatterThreads);
+        else if (stem) rc = launch(scatter_deconv<10, true>, S.P, S.blocks, lds, st, kScatterStemThreads);
+        else rc = launch(scatter_deconv<10, false>, S.P, S.blocks, lds, st, kScatterThreads);
+        if (rc != CKS_OK) return rc;
+        if (S.P.nBands > 1 && S.P.OVF > 0) {
+            BandHeadParams B{};
+            B.head = (const float *)ws; B.dX = dX;
+            B.N = N; B.IC = C; B.IH = H; B.IW = W; B.s = stride; B.p = padding; B.nBands = S.P.nBands; B.OVF = S.P.OVF;
+            const long long rows = (long long)N * (S.P.nBands - 1) * H;   // plan_scatter has checked that this fits 31 bits
+            B.rows = (int)rows;
+            B.xw = 1;
+            while (B.xw < S.P.OVF) B.xw *= 2;
+            const int rpb = kThreads / B.xw;
+            rc = launch(add_band_heads, B, (int)((rows + rpb - 1) / rpb), 0, st);
+            if (rc != CKS_OK) return rc;
+        }
+        if (S.rowheadBytes) {
+            RowHeadParams R{};
+            R.rowhead = S.P.rowhead; R.dX = dX;
+            R.N = N; R.IC = C; R.IH = H; R.IW = W; R.s = stride; R.p = padding; R.nBands = S.P.nBands; R.nTiles = S.P.nTiles;
+            R.SW = S.P.SW; R.SWlast = S.P.SWlast; R.HR = S.P.HR; R.stepsPerBlock = S.P.stepsPerBlock; R.blocks = S.blocks;
+            const int per = kThreads / kScatterRP;
+            rc = launch(add_row_heads, R, (S.blocks * S.P.HR + per - 1) / per, 0, st);
+        }
+        return rc;
     }
     rc = cks_kernel_split(Wt, (float *)ws, C, OC, FH, FW, stride, stream);
     if (rc != CKS_OK) return rc;

@@ -37,14 +37,19 @@ struct ScatterDeconvParams {
     const float *dY;
     const float *W;     // OHWI
     float *dX;
-    float *head;        // [N][nBands-1][IH][OVF]
+    float *head;        // [N][nBands-1][IH][OVF]: a band's share of the columns it has in common with its left neighbour
+    float *rowhead;     // [workgroups][HR][kScatterRP]: a workgroup's share of the rows its first segment has in
+                        // common with the rows above (written only if that segment starts inside a band)
     int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
     int nBands;         // ceil(OW / 16)
-    int nTiles;         // ceil(OH / 4)
-    int nFlush;         // output steps of 4*s dX rows each
+    int nTiles;         // ceil(OH / 4): steps of a band's sweep
+    int nFlush;         // output steps of 4*s dX rows each that a whole band needs
+    int steps;          // N * nBands * nTiles
+    int stepsPerBlock;  // consecutive steps (band-major) a workgroup works through
     int SW;             // floats of a dX row a band writes (from its first touched float)
     int SWlast;         // the same for the last band (includes dX columns no pixel reaches)
     int OVF;            // floats per row shared with the left neighbour: max(FW - s, 0) * IC
+    int HR;             // rows shared with the rows above: max(FH - s, 0)
     int slots;          // Q ring: dY rows kept
     int KP;             // OC rounded up to 16
 };
@@ -57,7 +62,7 @@ constexpr int kScatterRP = 128;    // floats per Q row
 constexpr int kScatterMaxTB = 4;   // taps per sub-kernel row and column: ceil(FW / s), ceil(FH / s) <= 4
 inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 {
-    return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + ((size_t)slots * FH + 1) * kScatterRP) * sizeof(float);
+    return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + ((size_t)slots * FH + 1 + 4) * kScatterRP) * sizeof(float);
 }
 
 // One pass of a stem MFMA wave (OC = 64: four K groups of 16): NBH column blocks of P for its dY
@@ -149,12 +154,11 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = blockIdx.x / P.nBands, c = blockIdx.x - n * P.nBands;
-    const int ow0 = c * 16;
     const int L = FW * IC, J = FH * L;
     const int rows4s = 4 * S;
+    float *Qdump = Qs + (SLOTS * FH + 1) * RP;   // [4][RP] receives what must go nowhere
 
-    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + (SLOTS * FH + 1) * RP;
+    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + (SLOTS * FH + 1 + 4) * RP;
     for (int i = tid; i < ldsFloats; i += THREADS) smem[i] = 0.f;
     __syncthreads();
     for (int i = tid; i < P.OC * J; i += THREADS) {
@@ -165,68 +169,90 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     }
     __syncthreads();
 
+    // This workgroup's share of the sweep steps, cut into segments at band ends.  A segment
+    // (band, steps [t0,t1)) composes the dX rows [4 t0 s, 4 t1 s + HR) (to the band's end if t1 is the
+    // last step); of those, the first HR rows (if t0 > 0) also receive from the steps above and go to
+    // rowhead, the last HR rows (if t1 is not the last step) are completed by the next segment's rowhead.
+    const int u0 = blockIdx.x * P.stepsPerBlock, u1 = min(u0 + P.stepsPerBlock, P.steps);
+    constexpr int DELAY = STEM ? 2 : 1;   // passes by which the output step trails a tile's MFMAs
+
     if (wave >= NCW) {
         // ------------------------------------------------------------ staging waves: step 2 and the stores
         // These waves issue few instructions, each of which would otherwise queue behind the MFMA
         // wave of the same SIMD.
         __builtin_amdgcn_s_setprio(3);
         const int pw = wave - NCW;
-        // Q float x of this band is dX float (ow0*s - p)*IC + x of its image row.  The image (and this
-        // band's side buffer) is one raw buffer, the row a scalar offset; lanes outside the row or not
-        // written by this band carry an offset beyond it.
-        const int sw = c == P.nBands - 1 ? P.SWlast : P.SW;
-        const int x0 = (ow0 * S - P.p) * IC, rowFloats = P.IW * IC;
-        int voffX[2], voffH[2];
+        const int rowFloats = P.IW * IC;
+        for (int u = u0; u < u1;) {
+            const int band = u / P.nTiles, t0 = u - band * P.nTiles, t1 = min(P.nTiles, t0 + (u1 - u));
+            const int n = band / P.nBands, c = band - n * P.nBands;
+            u += t1 - t0;
+            // Q float x of this band is dX float (16 c s - p)*IC + x of its image row.  The image (and
+            // the side buffers) are raw buffers, the row a scalar offset; lanes outside the row or not
+            // written by this band carry an offset beyond them.
+            const int sw = c == P.nBands - 1 ? P.SWlast : P.SW;
+            const int x0 = (c * 16 * S - P.p) * IC;
+            int voffX[2], voffH[2], voffR[2];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int x = lane + 64 * q;
-            const bool mine = x < sw && !(c > 0 && x < P.OVF) && x0 + x >= 0 && x0 + x < rowFloats;
-            voffX[q] = mine ? (x0 + x) * 4 : kBeyond;
-            voffH[q] = (c > 0 && x < P.OVF) ? x * 4 : kBeyond;
-        }
-        const __amdgpu_buffer_rsrc_t rsX =
-            __builtin_amdgcn_make_buffer_rsrc(P.dX + (long)n * P.IH * rowFloats, 0, P.IH * rowFloats * 4, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rsH = __builtin_amdgcn_make_buffer_rsrc(
-            P.head + ((long)n * (P.nBands - 1) + max(c - 1, 0)) * P.IH * P.OVF, 0, c > 0 ? P.IH * P.OVF * 4 : 0, 0x00020000);
-        // rows [k*4s, (k+1)*4s) are complete once step 1 of tile k is done: one pass after the tile's
-        // MFMAs, two where step 1 trails the MFMAs by a pass
-        constexpr int DELAY = STEM ? 2 : 1;
-        for (int i = 0; i < P.nFlush + DELAY; ++i) {
-            const int k = i - DELAY;
-            if (k >= 0 && k < P.nFlush) {
+            for (int q = 0; q < 2; ++q) {
+                const int x = lane + 64 * q;
+                const bool inrow = x < sw && x0 + x >= 0 && x0 + x < rowFloats;
+                voffX[q] = (inrow && !(c > 0 && x < P.OVF)) ? (x0 + x) * 4 : kBeyond;
+                voffH[q] = (c > 0 && x < P.OVF) ? x * 4 : kBeyond;
+                voffR[q] = inrow ? x * 4 : kBeyond;
+            }
+            const __amdgpu_buffer_rsrc_t rsX =
+                __builtin_amdgcn_make_buffer_rsrc(P.dX + (long)n * P.IH * rowFloats, 0, P.IH * rowFloats * 4, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rsH = __builtin_amdgcn_make_buffer_rsrc(
+                P.head + ((long)n * (P.nBands - 1) + max(c - 1, 0)) * P.IH * P.OVF, 0, c > 0 ? P.IH * P.OVF * 4 : 0, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rsR = __builtin_amdgcn_make_buffer_rsrc(
+                P.rowhead + (long)blockIdx.x * P.HR * RP, 0, t0 > 0 ? P.HR * RP * 4 : 0, 0x00020000);
+            const bool last = t1 == P.nTiles;
+            const int rowBeg = t0 * rows4s, rowEnd = last ? P.nFlush * rows4s : t1 * rows4s + P.HR;
+            const int kEnd = (rowEnd + rows4s - 1) / rows4s;
+            const int ohBeg = 4 * t0, ohEnd = min(P.OH, 4 * t1);
+            for (int i = t0; i < kEnd + DELAY; ++i) {
+                const int k = i - DELAY;   // rows [k*4s, (k+1)*4s) are complete once step 1 of tile k is done
+                if (k >= t0) {
 #pragma unroll 2
-                for (int r = pw; r < rows4s; r += 4) {
-                    const int row = k * rows4s + r;   // = ih + p
-                    const int ih = row - P.p;
-                    if (ih < 0 || ih >= P.IH) continue;   // uniform
-                    // row = oh*s + fh: fh = r mod s + t*s, oh = 4k + r/s - t.  All reads are issued before the
-                    // first add; a term that does not exist reads the zero row behind the ring.
-                    const int fh0 = r % S, ohTop = 4 * k + r / S;
-                    float v0[MAXTB], v1[MAXTB];
+                    for (int r = pw; r < rows4s; r += 4) {
+                        const int row = k * rows4s + r;   // = ih + p
+                        const int ih = row - P.p;
+                        if (row >= rowEnd || ih < 0 || ih >= P.IH) continue;   // uniform
+                        // row = oh*s + fh: fh = r mod s + t*s, oh = 4k + r/s - t.  All reads are issued before
+                        // the first add; a term that does not exist reads the zero row behind the ring.
+                        const int fh0 = r % S, ohTop = 4 * k + r / S;
+                        float v0[MAXTB], v1[MAXTB];
 #pragma unroll
-                    for (int t = 0; t < MAXTB; ++t) {
-                        const int fh = fh0 + t * S, oh = ohTop - t;
-                        const bool ok = fh < FH && oh >= 0 && oh < P.OH;   // uniform
-                        const float *qp = (ok ? Qs + ((oh % SLOTS) * FH + fh) * RP : Qzero) + lane;
-                        v0[t] = qp[0];
-                        v1[t] = qp[64];
-                    }
-                    const float sum0 = (v0[0] + v0[1]) + (v0[2] + v0[3]);
-                    const float sum1 = (v1[0] + v1[1]) + (v1[2] + v1[3]);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsX, voffX[0], ih * rowFloats * 4, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsX, voffX[1], ih * rowFloats * 4, 0);
-                    if (c > 0) {
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsH, voffH[0], ih * P.OVF * 4, 0);
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsH, voffH[1], ih * P.OVF * 4, 0);
+                        for (int t = 0; t < MAXTB; ++t) {
+                            const int fh = fh0 + t * S, oh = ohTop - t;
+                            const bool ok = fh < FH && oh >= ohBeg && oh < ohEnd;   // uniform
+                            const float *qp = (ok ? Qs + ((oh % SLOTS) * FH + fh) * RP : Qzero) + lane;
+                            v0[t] = qp[0];
+                            v1[t] = qp[64];
+                        }
+                        const float sum0 = (v0[0] + v0[1]) + (v0[2] + v0[3]);
+                        const float sum1 = (v1[0] + v1[1]) + (v1[2] + v1[3]);
+                        if (t0 > 0 && row < rowBeg + P.HR) {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsR, voffR[0], (row - rowBeg) * RP * 4, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsR, voffR[1], (row - rowBeg) * RP * 4, 0);
+                        } else {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsX, voffX[0], ih * rowFloats * 4, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsX, voffX[1], ih * rowFloats * 4, 0);
+                            if (c > 0) {
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsH, voffH[0], ih * P.OVF * 4, 0);
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsH, voffH[1], ih * P.OVF * 4, 0);
+                            }
+                        }
                     }
                 }
+                __syncthreads();
             }
-            __syncthreads();
         }
         return;
     }
 
-    // ---------------------------------------------------------------- MFMA waves: wave w owns dY row 4i + w of step i
+    // ---------------------------------------------------------------- MFMA waves: a wave owns dY row 4i + wrow of step i
     // 16x16x4 MFMA: lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16];
     // result register r holds D[m = 4*(l/16) + r][n = l%16].
     // Stem: waves 0-3 take filter rows 0-3 (column blocks 0-5) of dY rows 0-3 of the step, waves 4-7
@@ -239,17 +265,7 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     int a_voff[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) a_voff[u] = (16 * u + 4 * lk < P.OC) ? (lm * P.OC + 16 * u + 4 * lk) * 4 : kBeyond;
-    const int a_bytes = min(16, P.OW - ow0) * P.OC * 4;
     float4 areg[4];
-    auto fetch = [&](int i) {
-        const int oh = 4 * i + wrow;
-        const long off = (((long)n * P.OH + min(oh, P.OH - 1)) * P.OW + ow0) * P.OC;
-        const __amdgpu_buffer_rsrc_t rs =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + off), 0, oh < P.OH ? a_bytes : 0, 0x00020000);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            areg[u] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff[u], 0, 0));
-    };
     // step 1, lane constants: ring float x = lane + 64q is pixel column pwx = x / IC (= v*s + b), channel ic
     float *Pw = Ps + (wrow * NB * 16 + colBase) * PP;   // this wave's columns of its row's scratch
     const float *gat[2][MAXTB];
@@ -270,66 +286,85 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     float *Pst = Pw + lm * PP + 4 * lk;   // + b*16*PP: P[pixels 4lk..4lk+3][column 16b + lm]
     const float *Bp = Bs + (colBase + lm) * LDK + 4 * lk;
 
-    fetch(0);
-    if constexpr (STEM) {
-        for (int i = 0; i <= P.nFlush + 1; ++i) {
-            // Q rows of dY row 4(i-1) + wrow; in the first pass the scratch is still all zero and the
-            // zero row receives zeros
-            float *qrow = (i > 0 ? Qs + (((4 * (i - 1) + wrow) % SLOTS) * 7 + fhBase) * RP : Qs + SLOTS * 7 * RP) + lane;
-            if (i < P.nTiles) {   // uniform
-                float4 a[4];
+    for (int u = u0; u < u1;) {
+        const int band = u / P.nTiles, t0 = u - band * P.nTiles, t1 = min(P.nTiles, t0 + (u1 - u));
+        const int n = band / P.nBands, c = band - n * P.nBands;
+        u += t1 - t0;
+        const int ow0 = c * 16;
+        const int a_bytes = min(16, P.OW - ow0) * P.OC * 4;
+        auto fetch = [&](int i) {
+            const int oh = 4 * i + wrow;
+            const long off = (((long)n * P.OH + min(oh, P.OH - 1)) * P.OW + ow0) * P.OC;
+            const __amdgpu_buffer_rsrc_t rs =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + off), 0, oh < P.OH ? a_bytes : 0, 0x00020000);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) a[u] = areg[u];
-                if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
-                if (half == 0) scatter_stem_pass<6, 4, true>(a, Bp, gat, fhStride, qrow, Pst);
-                else scatter_stem_pass<4, 3, true>(a, Bp, gat, fhStride, qrow, Pst);
-            } else if (i == P.nTiles) {
-                // the last dY rows: step 1 on its own
-                float4 a[4];
-                if (half == 0) scatter_stem_pass<6, 4, false>(a, Bp, gat, fhStride, qrow, Pst);
-                else scatter_stem_pass<4, 3, false>(a, Bp, gat, fhStride, qrow, Pst);
+            for (int uu = 0; uu < 4; ++uu)
+                areg[uu] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff[uu], 0, 0));
+        };
+        const bool last = t1 == P.nTiles;
+        const int rowEnd = last ? P.nFlush * rows4s : t1 * rows4s + P.HR;
+        const int kEnd = (rowEnd + rows4s - 1) / rows4s;
+        fetch(t0);
+        if constexpr (STEM) {
+            for (int i = t0; i < kEnd + DELAY; ++i) {
+                // Q rows of dY row 4(i-1) + wrow.  In a segment's first pass the scratch holds nothing of
+                // this segment: what is gathered goes to the dump row.
+                float *qrow = (i > t0 ? Qs + (((4 * (i - 1) + wrow) % SLOTS) * 7 + fhBase) * RP : Qdump) + lane;
+                if (i < t1) {   // uniform
+                    float4 a[4];
+#pragma unroll
+                    for (int uu = 0; uu < 4; ++uu) a[uu] = areg[uu];
+                    if (i + 1 < t1) fetch(i + 1);   // in flight during this step's MFMAs
+                    if (half == 0) scatter_stem_pass<6, 4, true>(a, Bp, gat, fhStride, qrow, Pst);
+                    else scatter_stem_pass<4, 3, true>(a, Bp, gat, fhStride, qrow, Pst);
+                } else if (i == t1) {
+                    // the segment's last dY rows: step 1 on its own
+                    float4 a[4];
+                    if (half == 0) scatter_stem_pass<6, 4, false>(a, Bp, gat, fhStride, qrow, Pst);
+                    else scatter_stem_pass<4, 3, false>(a, Bp, gat, fhStride, qrow, Pst);
+                }
+                __syncthreads();
             }
-            __syncthreads();
-        }
-    } else {
-        for (int i = 0; i <= P.nFlush; ++i) {
-            if (i < P.nTiles) {   // uniform
-                floatx4 acc[NB];
+        } else {
+            for (int i = t0; i < kEnd + DELAY; ++i) {
+                if (i < t1) {   // uniform
+                    floatx4 acc[NB];
 #pragma unroll
-                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-                float4 a[4];
+                    for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    float4 a[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) a[u] = areg[u];
-                if (i + 1 < P.nTiles) fetch(i + 1);   // in flight during this step's MFMAs
+                    for (int uu = 0; uu < 4; ++uu) a[uu] = areg[uu];
+                    if (i + 1 < t1) fetch(i + 1);   // in flight during this step's MFMAs
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (u < KU) {
+                    for (int uu = 0; uu < 4; ++uu) {
+                        if (uu < KU) {
 #pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-                            const float4 w4 = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * u);
-                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, w4.x, acc[b], 0, 0, 0);
-                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, w4.y, acc[b], 0, 0, 0);
-                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, w4.z, acc[b], 0, 0, 0);
-                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, w4.w, acc[b], 0, 0, 0);
+                            for (int b = 0; b < NB; ++b) {
+                                const float4 w4 = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * uu);
+                                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[uu].x, w4.x, acc[b], 0, 0, 0);
+                                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[uu].y, w4.y, acc[b], 0, 0, 0);
+                                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[uu].z, w4.z, acc[b], 0, 0, 0);
+                                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[uu].w, w4.w, acc[b], 0, 0, 0);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+                    // the scratch is private to this wave: its LDS accesses complete in order
+                    float *qrow = Qs + (((4 * i + wrow) % SLOTS) * FH) * RP + lane;
+                    for (int fh = 0; fh < FH; ++fh) {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            float sum = 0.f;
+#pragma unroll
+                            for (int tb = 0; tb < MAXTB; ++tb) sum += gat[q][tb][fh * fhStride];
+                            qrow[fh * RP + 64 * q] = sum;
                         }
                     }
                 }
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
-                // the scratch is private to this wave: its LDS accesses complete in order
-                float *qrow = Qs + (((4 * i + wave) % SLOTS) * FH) * RP + lane;
-                for (int fh = 0; fh < FH; ++fh) {
-#pragma unroll
-                    for (int q = 0; q < 2; ++q) {
-                        float sum = 0.f;
-#pragma unroll
-                        for (int tb = 0; tb < MAXTB; ++tb) sum += gat[q][tb][fh * fhStride];
-                        qrow[fh * RP + 64 * q] = sum;
-                    }
-                }
+                __syncthreads();
             }
-            __syncthreads();
         }
     }
 }
@@ -339,21 +374,46 @@ struct BandHeadParams {
     const float *head;
     float *dX;
     int N, IC, IH, IW, s, p, nBands, OVF;
-    long total;   // N * (nBands-1) * IH * OVF
+    int rows;     // N * (nBands-1) * IH rows of OVF floats
+    int xw;       // threads per row: power of two >= OVF, <= 256
 };
 
 __global__ void __launch_bounds__(kThreads) add_band_heads(const BandHeadParams P)
 {
-    const long i = (long)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= P.total) return;
-    const int x = (int)(i % P.OVF);
-    long t = i / P.OVF;
-    const int ih = (int)(t % P.IH);
-    t /= P.IH;
-    const int c = (int)(t % (P.nBands - 1)) + 1, n = (int)(t / (P.nBands - 1));
+    const int rpb = kThreads / P.xw;   // rows per workgroup
+    const int row = blockIdx.x * rpb + threadIdx.x / P.xw, x = threadIdx.x % P.xw;
+    if (row >= P.rows || x >= P.OVF) return;
+    const int ih = row % P.IH, t = row / P.IH;
+    const int c = t % (P.nBands - 1) + 1, n = t / (P.nBands - 1);
     const int col = (16 * c * P.s - P.p) * P.IC + x;
     if (col < 0 || col >= P.IW * P.IC) return;
-    P.dX[((long)n * P.IH + ih) * P.IW * P.IC + col] += P.head[i];
+    P.dX[((long)n * P.IH + ih) * P.IW * P.IC + col] += P.head[(long)row * P.OVF + x];
+}
+
+// dX rows [4 t0 s, 4 t0 s + HR) of the band a workgroup's first segment lies in += that workgroup's
+// rowhead (if the segment starts inside the band).  The host has checked that no two workgroups'
+// row heads meet in one dX element, so every element is added to by one thread only.
+struct RowHeadParams {
+    const float *rowhead;
+    float *dX;
+    int N, IC, IH, IW, s, p, nBands, nTiles, SW, SWlast, HR, stepsPerBlock, blocks;
+};
+
+__global__ void __launch_bounds__(kThreads) add_row_heads(const RowHeadParams P)
+{
+    const int per = kThreads / kScatterRP;   // rows per workgroup of this kernel
+    const int hr = blockIdx.x * per + threadIdx.x / kScatterRP, x = threadIdx.x % kScatterRP;
+    if (hr >= P.blocks * P.HR) return;
+    const int g = hr / P.HR, r = hr - g * P.HR;
+    const int u0 = g * P.stepsPerBlock;
+    const int band = u0 / P.nTiles, t0 = u0 - band * P.nTiles;
+    if (t0 == 0) return;
+    const int n = band / P.nBands, c = band - n * P.nBands;
+    const int ih = t0 * 4 * P.s + r - P.p;
+    const int sw = c == P.nBands - 1 ? P.SWlast : P.SW;
+    const int col = (16 * c * P.s - P.p) * P.IC + x;
+    if (ih < 0 || ih >= P.IH || x >= sw || col < 0 || col >= P.IW * P.IC) return;
+    P.dX[((long)n * P.IH + ih) * P.IW * P.IC + col] += P.rowhead[(long)hr * kScatterRP + x];
 }
 
 }  // namespace cks
