@@ -155,9 +155,12 @@ def bench_layer(L, steps, warmup, with_kernels=True):
     if with_kernels:
         B.k_split(); B.k_wgrad_main()
         ker = {}
-        for name, fn in (("rowrun_gemm<fwd>", B.fwd), ("pack_filter<split>", B.k_split),
-                         ("rowrun_gemm<deconv>", B.k_deconv_main), ("pixel_gemm", B.k_wgrad_main),
-                         ("reduce_slices", B.k_reduce)):
+        # the step's own kernels (cfg1: one launch each for forward and input gradient, which reads the
+        # filter in place; main + reduce for the filter gradient) and the stage entry points of the
+        # pre-split mode (kernel split, Stage 2&3 on a split filter)
+        for name, fn in (("rowrun_gemm<fwd>", B.fwd), ("rowrun_gemm<deconv>", B.deconv), ("pixel_gemm", B.k_wgrad_main),
+                         ("reduce_slices", B.k_reduce), ("pack_filter<split>", B.k_split),
+                         ("rowrun_gemm<deconv, presplit>", B.k_deconv_main)):
             ker[name] = B.time_ms(fn, steps, warmup)
         out["kernel_ms"] = ker
     return B, out
@@ -311,7 +314,7 @@ def main():
     mains = {k: r["kernel_ms"][k] for k in ("rowrun_gemm<fwd>", "rowrun_gemm<deconv>", "pixel_gemm")}
     dom = max(mains, key=mains.get)
     achieved = B.useful_flops / mains[dom] / 1e9
-    prefix = {"rowrun_gemm<fwd>": "cks::rowrun_gemm<0", "rowrun_gemm<deconv>": "cks::rowrun_gemm<1",
+    prefix = {"rowrun_gemm<fwd>": "cks::rowrun_gemm<0", "rowrun_gemm<deconv>": "cks::rowrun_gemm<2",
               "pixel_gemm": "cks::pixel_gemm"}[dom]
     line = {
         "metric": METRIC, "value": r["step_tflops"], "unit": "TFLOP/s", "n_gpus": 1,

@@ -80,7 +80,16 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
                    void *ws, size_t ws_bytes, void *stream);
 
 /* KS-deconv-V2 (Section IV.B; Algorithm 2 Stage 1, Algorithm 2B Stage 2&3).
- * Runs cks_kernel_split into the workspace, then cks_deconv2d_presplit.
+ * The sub-kernels of Stage 1 are either taken straight from Wt (sub-kernel
+ * (y,x)'s tap (ch,cw) is filter tap (y + (CH-1-ch) s, x + (CW-1-cw) s); used when
+ * OC is a multiple of 32, C a multiple of 4 and dY, Wt are 16-byte aligned), or
+ * written to the workspace by cks_kernel_split and consumed by
+ * cks_deconv2d_presplit.  Layers with C < 8 and OC <= 64 run Stage 2&3
+ * tap-stationary and compose the result in on-chip memory; they use the
+ * workspace for the rows and columns neighbouring workgroups share.  The
+ * workspace must always have cks_deconv2d_workspace bytes; the result does not
+ * depend on which variant runs beyond rounding, and every variant is
+ * reproducible bit for bit.
  * dY [N,OH,OW,OC] in, Wt [OC,FH,FW,C] in, dX [N,H,W,C] out. */
 int cks_deconv2d(const float *dY, const float *Wt, float *dX,
                  int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,

@@ -108,11 +108,26 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     const long long kch = OP == OP_FWD ? P.IC : P.OC;
     const long long rowA = OP == OP_FWD ? (long long)P.IH * P.IW * P.IC : (long long)P.OH * P.OW * P.OC;
     const long long rowB = OP == OP_FWD ? (long long)P.FH * P.FW * P.IC : (long long)P.CHp * P.CWp * P.OC;
-    const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (rowB * BN + rowB) * 4 < (1LL << 31) &&
-                      !getenv("CKS_TUNE_NO_FAST_LOADS");
-    if (fast) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
-    if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
-    return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_SCALAR>, P, (int)blocks, lds, st);
+    if constexpr (OP == OP_DECONV_W) {
+        // the caller has checked deconv_in_place_ok: only the fast-load variant exists
+        return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
+    } else {
+        const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (rowB * BN + rowB) * 4 < (1LL << 31) &&
+                          !getenv("CKS_TUNE_NO_FAST_LOADS");
+        if (fast) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
+        if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
+        return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_SCALAR>, P, (int)blocks, lds, st);
+    }
+}
+
+// KS-deconv can take its sub-kernels straight from the OHWI filter (no Stage 1 launch, no
+// workspace) when the fast-load variant applies: whole 32-channel chunks of OC, 16-byte vectors,
+// tile rows of dY within 2 GiB of the first (for the largest tile, 128 rows), the filter below 2 GiB.
+bool deconv_in_place_ok(const Geo &g, const float *dY, const float *Wt)
+{
+    const long long rowA = (long long)g.OH * g.OW * g.OC, w = (long long)g.OC * g.FH * g.FW * g.C;
+    return g.OC % 32 == 0 && g.C % 4 == 0 && aligned16(dY) && aligned16(Wt) && rowA * 129 * 4 < (1LL << 31) &&
+           w * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS") && !getenv("CKS_TUNE_SPLIT_DECONV");
 }
 
 template <int OP>
@@ -605,6 +620,8 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
         }
         return rc;
     }
+    if (deconv_in_place_ok(g, dY, Wt))
+        return dispatch_rowrun<OP_DECONV_W>(rowrun_params<OP_DECONV_W>(g, dY, Wt, dX), N, C, true, (hipStream_t)stream);
     rc = cks_kernel_split(Wt, (float *)ws, C, OC, FH, FW, stride, stream);
     if (rc != CKS_OK) return rc;
     return cks_deconv2d_presplit(dY, (const float *)ws, dX, N, C, H, W, OC, FH, FW, stride, padding, stream);

@@ -14,6 +14,10 @@
 //
 //   ConvV2:    A = X,  B = W[oc][fh][fw][ic]              run over (fw, ic)
 //   KS-deconv: A = dY, B = Cs[y][x][ic][ch][cw][oc]       run over (cw, oc)
+//   KS-deconv without Stage 1: A = dY, B = W itself.  Sub-kernel (y,x)'s tap (ch,cw) is the filter tap
+//              (y + (CH-1-ch) s, x + (CW-1-cw) s); for it W[oc][fh][fw][ic] is a K x N matrix (oc x ic) with
+//              N contiguous.  It is staged into LDS as it lies (K-major) and the B fragments are read one
+//              float per MFMA instead of four: Stage 1 then costs nothing at all.
 //
 // So a workgroup owns (position, 128/64 batch rows, 128/64/32 channels), knows its
 // trim as scalars, and walks  nruns x ceil(L/32)  K-chunks; trimming costs
@@ -25,7 +29,8 @@
 
 namespace cks {
 
-enum { OP_FWD = 0, OP_DECONV = 1 };
+// OP_DECONV_W: KS-deconv Stage 2&3 that takes its sub-kernels straight from the OHWI filter (see below)
+enum { OP_FWD = 0, OP_DECONV = 1, OP_DECONV_W = 2 };
 
 struct RowRunParams {
     const float *A;   // X (fwd) or dY (deconv)
@@ -48,6 +53,7 @@ struct RowRunParams {
 struct RunSet {
     long a0, b0, o0;          // float offsets of the first run in A-row 0, B-row 0, Out-row 0
     long aRun, bRun;          // float distance between consecutive runs
+    long bCw;                 // OP_DECONV_W: float distance between consecutive cw (negative: the rotation)
     long strideA, strideB, strideO;
     int nruns, L, NC;         // runs, floats per run, number of output channels
 };
@@ -72,6 +78,7 @@ template <int OP>
 __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 {
     RunSet R;
+    R.bCw = 0;
     if (OP == OP_FWD) {
         // Algorithm 1: trim [fh_s,fh_e) x [fw_s,fw_e) of the filter at (oh,ow).
         const int oh = ph, ow = pw;
@@ -104,9 +111,17 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         R.a0 = ((long)(oh_s + ch_s) * P.OW + (ow_s + cw_s)) * P.OC;
         R.aRun = (long)P.OW * P.OC;
         R.strideA = (long)P.OH * P.OW * P.OC;
-        R.strideB = (long)P.CHp * P.CWp * P.OC;
-        R.b0 = (long)(y * P.s + x) * P.IC * R.strideB + ((long)ch_s * P.CWp + cw_s) * P.OC;
-        R.bRun = (long)P.CWp * P.OC;
+        if (OP == OP_DECONV_W) {
+            // run r is sub-kernel row ch_s + r = filter row y + (CH-1-ch_s-r) s; likewise the columns
+            R.strideB = (long)P.FH * P.FW * P.IC;
+            R.b0 = ((long)(y + (CH - 1 - ch_s) * P.s) * P.FW + (x + (CW - 1 - cw_s) * P.s)) * P.IC;
+            R.bRun = -(long)P.s * P.FW * P.IC;
+            R.bCw = -(long)P.s * P.IC;
+        } else {
+            R.strideB = (long)P.CHp * P.CWp * P.OC;
+            R.b0 = (long)(y * P.s + x) * P.IC * R.strideB + ((long)ch_s * P.CWp + cw_s) * P.OC;
+            R.bRun = (long)P.CWp * P.OC;
+        }
         R.o0 = ((long)ih * P.IW + iw) * P.IC;   // Stage 3: the class result lands at its own (ih,iw)
         R.strideO = (long)P.IH * P.IW * P.IC;
         R.NC = P.IC;
@@ -152,6 +167,11 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
     constexpr int PA = BM / 32, PB = BN / 32;
     static_assert(WAVES_M * WAVES_N == 4 && TM >= 1 && TN >= 1, "4 waves per workgroup");
+    // OP_DECONV_W: B chunk = 32 output channels (K) x BN input channels, staged K-major
+    constexpr bool BK = OP == OP_DECONV_W;
+    constexpr int LDB = BN + 4, TPR = BN / 4, RPP = kThreads / TPR;   // floats per k-row, threads / rows per staging pass
+    static_assert(!BK || LOAD == LOAD_FAST, "the filter is read in place only by the fast-load variant");
+    static_assert(!BK || 2 * KC * LDB <= 2 * BN * LDK, "the K-major B buffers fit the LDS of the row-major ones");
 
     extern __shared__ __align__(16) float smem[];
     float *As = smem;                 // [2][BM][LDK]
@@ -165,7 +185,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     int ph = item / P.itemsW, pw = item % P.itemsW;
     ph = (ph + P.rotH) % P.itemsH;
     pw = (pw + P.rotW) % P.itemsW;
-    if (OP == OP_DECONV) {
+    if (OP != OP_FWD) {
         ph = class_major_index(ph, P.IH, P.s, P.p);
         pw = class_major_index(pw, P.IW, P.s, P.p);
     }
@@ -201,16 +221,25 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
         pa[i] = P.A + (long)r * R.strideA + R.a0 + lc;
         va[i] = (unsigned)(((long)(r - m0) * R.strideA + lc) * 4);
     }
+    const int brow = tid / TPR, bcol = (tid % TPR) * 4;   // BK: k-row (output channel of the chunk) and column of this thread
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
         const int c = min(n0 + lr + 32 * i, R.NC - 1);
         pb[i] = P.B + (long)c * R.strideB + R.b0 + lc;
-        vb[i] = (unsigned)(((long)(c - n0) * R.strideB + lc) * 4);
+        vb[i] = BK ? (unsigned)(((long)(brow + RPP * i) * R.strideB + bcol) * 4)
+                   : (unsigned)(((long)(c - n0) * R.strideB + lc) * 4);
     }
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(P.A + (long)min(m0, P.N - 1) * R.strideA + R.a0), 0, -1, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(P.B + (long)min(n0, R.NC - 1) * R.strideB + R.b0), 0, -1, 0x00020000);
+    // BK: the filter from column n0 on, as a buffer of its true size: columns past IC in the last
+    // filter row of all are out of range and read as zero (elsewhere they are the next tap's, and
+    // feed output columns that are never stored)
+    const __amdgpu_buffer_rsrc_t rsB =
+        BK ? __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + n0), 0,
+                                               (int)(((long)P.OC * R.strideB - n0) * 4), 0x00020000)
+           : __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + (long)min(n0, R.NC - 1) * R.strideB + R.b0), 0, -1,
+                                               0x00020000);
+    const int ocChunks = P.OC / KC;   // BK: chunks per cw
 
     // One register set: the loads of chunk t+1 are issued before chunk t is
     // multiplied out of LDS and stored to the other LDS buffer after it.  (A
@@ -218,10 +247,13 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     struct Stage { float4 a[PA], b[PB]; };
     Stage S0;
     // `live` false: nothing is read; the masked modes then stage zeros.
+    int cwi = 0, occ = 0;   // BK: the chunk being loaded is output channels 32*occ.. of sub-kernel column cw_s + cwi
     auto gload = [&](Stage &S, int run, int ck, bool live) {
         if (LOAD == LOAD_FAST) {
             if (!live) return;   // uniform
-            const int sa = (int)((run * R.aRun + ck * KC) * 4), sb = (int)((run * R.bRun + ck * KC) * 4);
+            const int sa = (int)((run * R.aRun + ck * KC) * 4);
+            const int sb = BK ? (int)((R.b0 + run * R.bRun + cwi * R.bCw + (long)occ * KC * R.strideB) * 4)
+                              : (int)((run * R.bRun + ck * KC) * 4);
 #pragma unroll
             for (int i = 0; i < PA; ++i)
                 S.a[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsA, va[i], sa, 0));
@@ -239,12 +271,15 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     };
     // buf is a compile-time constant in the loop below, so every LDS access is
     // "thread base + immediate"
-    float *const Aw = As + lr * LDK + lc, *const Bw = Bs + lr * LDK + lc;
+    float *const Aw = As + lr * LDK + lc, *const Bw = Bs + lr * LDK + lc, *const Bwk = Bs + brow * LDB + bcol;
     auto sstore = [&](const Stage &S, int buf) {
 #pragma unroll
         for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(Aw + (buf * BM + 32 * i) * LDK) = S.a[i];
 #pragma unroll
-        for (int i = 0; i < PB; ++i) *reinterpret_cast<float4 *>(Bw + (buf * BN + 32 * i) * LDK) = S.b[i];
+        for (int i = 0; i < PB; ++i) {
+            if (BK) *reinterpret_cast<float4 *>(Bwk + (buf * KC + RPP * i) * LDB) = S.b[i];
+            else *reinterpret_cast<float4 *>(Bw + (buf * BN + 32 * i) * LDK) = S.b[i];
+        }
     };
 
     // MFMA fragments: lane l reads 4 consecutive k of row (l%32); the two lane
@@ -252,6 +287,18 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     // shorter than 32 is zero-filled in LDS, so every chunk runs the same 4 steps
     // and the accumulators never leave their registers.
     const float *const Ar = As + (wm * TM * 32 + frow) * LDK + fk, *const Br = Bs + (wn * TN * 32 + frow) * LDK + fk;
+    // K-major B: one base per (buffer, k-group of 8), so that the four rows a lane reads are within the
+    // 1 KB an LDS read pair can address beyond its base (anything larger costs a VALU add in the loop)
+    typedef __attribute__((address_space(3))) const float lds_cfloat;
+    lds_cfloat *brk[2][KC / 8];   // LDS addresses, made opaque so that each stays in a register of its own
+#pragma unroll
+    for (int bf = 0; bf < 2; ++bf)
+#pragma unroll
+        for (int kk = 0; kk < KC / 8; ++kk) {
+            lds_cfloat *q = (lds_cfloat *)(Bs + ((bf * KC + kk * 8) + fk) * LDB + wn * TN * 32 + frow);
+            asm volatile("" : "+v"(q));
+            brk[bf][kk] = q;
+        }
     auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < KC / 8; ++kk) {
@@ -259,7 +306,15 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 #pragma unroll
             for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4 *>(Ar + (buf * BM + i * 32) * LDK + kk * 8);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4 *>(Br + (buf * BN + j * 32) * LDK + kk * 8);
+            for (int j = 0; j < TN; ++j) {
+                if (BK) {
+                    // K-major: the lane's four k (fk .. fk+3) are four rows
+                    lds_cfloat *q = brk[buf][kk] + j * 32;
+                    b[j] = float4{q[0], q[LDB], q[2 * LDB], q[3 * LDB]};
+                } else {
+                    b[j] = *reinterpret_cast<const float4 *>(Br + (buf * BN + j * 32) * LDK + kk * 8);
+                }
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -272,7 +327,10 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     };
 
     int run = 0, ck = 0;   // chunk being loaded
-    auto next_chunk = [&]() { if (++ck == cpr) { ck = 0; ++run; } };
+    auto next_chunk = [&]() {
+        if (BK && ++occ == ocChunks) { occ = 0; ++cwi; }
+        if (++ck == cpr) { ck = 0; ++run; cwi = 0; occ = 0; }
+    };
     // The loop body handles two chunks with literal buffer numbers (all LDS
     // addresses become immediates) and no branch around the MFMAs (so the
     // accumulators stay in place).  An odd chunk count is peeled off in front:
