@@ -146,6 +146,12 @@ MID = [
     ("rgb_4x4_s3", 3, 3, 17, 35, 8, 4, 4, 3, 1),
     ("rgb_wide", 2, 3, 9, 70, 4, 3, 3, 1, 1),
     ("two_ch_6x6_s2", 3, 2, 15, 18, 60, 6, 6, 2, 2),
+    # OC a multiple of 32: the input gradient reads its sub-kernels from the filter in place
+    ("inplace_s2", 70, 36, 11, 12, 96, 3, 3, 2, 1),
+    ("inplace_s3_5x4", 33, 20, 13, 11, 32, 5, 4, 3, 2),
+    ("inplace_c_ragged", 40, 100, 7, 7, 160, 3, 3, 1, 1),
+    ("inplace_stride_gt_filter", 10, 8, 9, 9, 32, 1, 1, 2, 0),
+    ("inplace_4x4_s2_remainder", 9, 12, 10, 9, 64, 4, 4, 2, 1),
     # more bands than compute units: the input gradient's workgroups take runs of sweep steps that
     # start and end inside bands, and the rows two runs share are added afterwards
     ("stem_row_heads", 37, 3, 24, 224, 64, 7, 7, 2, 3),
