@@ -304,10 +304,10 @@ WgradPlan plan_wgrad(const Geo &g)
         }
     }
     // 64-wide channel tiles; 128 output channels per tile only for a middling number of tiles
-    // (measured: 128x128 tiles lose 5-8 points on every layer, 128x64 gain 3 on 576 tiles and
-    // lose 4 on 1600)
+    // and a long contraction axis (measured: 128x128 tiles lose 5-8 points on every layer, 128x64
+    // gain 3 on 576 tiles with 12544 pixels, lose 4 on 576 tiles with 4096 pixels or on 1600 tiles)
     const long long tiles64 = (long long)g.FH * g.FW * ((g.OC + 63) / 64) * ((g.C + 63) / 64);
-    w.variant = (g.OC >= 96 && tiles64 > 128 && tiles64 <= 1024) ? 5 : 4;
+    w.variant = (g.OC >= 96 && tiles64 > 128 && tiles64 <= 1024 && (long long)g.N * g.OH * g.OW >= 8192) ? 5 : 4;
     long long gz_override = 0;
     if (const char *t = tune) {
         int v = -1, z = 0;
