@@ -320,6 +320,46 @@ def test_wgrad_is_reproducible_bit_for_bit(cks):
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
+WGRAD_STAGES = [
+    ("general", 130, 40, 11, 12, 68, 3, 3, 2, 1),        # one tile per tap, many segments
+    ("patch", 40, 16, 9, 10, 70, 3, 3, 1, 1),            # all taps in one tile
+    ("stem", 6, 3, 40, 37, 64, 7, 7, 2, 3),              # input strip in LDS, one segment per workgroup
+]
+
+
+@pytest.mark.parametrize("geo", WGRAD_STAGES, ids=[g[0] for g in WGRAD_STAGES])
+def test_wgrad_stage_entry_points(cks, oracle, geo):
+    """Map step and reduce step of the filter gradient on their own: the segments' partial sums add
+    up to the oracle's result (exactly, on integer inputs); on real inputs the reduce kernel returns
+    their sum to fp32 rounding, the same bits every time."""
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer(*geo)
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+    gz = cks.cks_dilated_conv2d_wgrad_segments(*g)
+    print("geometry", geo, "segments", gz, flush=True)
+    for kind in ("int", "normal"):
+        X, W, dY = synth.make_inputs(L, kind, 11)
+        part = nan_like((gz, L.OC, L.FH, L.FW, L.IC))
+        cks.cks_dilated_conv2d_wgrad_partials(dev(X), dev(dY), part, L.FH, L.FW, L.stride, L.padding)
+        dW, dW2 = nan_like(W.shape), nan_like(W.shape)
+        cks.cks_reduce_partials(part, dW)
+        cks.cks_reduce_partials(part, dW2)
+        torch.cuda.synchronize()
+        ph = part.cpu().numpy().astype(np.float64)
+        assert np.isfinite(ph).all(), "a segment left part of its slice unwritten"
+        got = dW.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), dW2.cpu().numpy().view(np.uint32))
+        if kind == "int":
+            want = oracle.wgrad(X, dY, L.FH, L.FW, L.stride, L.padding)
+            assert_exact(ph.sum(0).astype(np.float32), want, "%s: sum of the partial slices" % L.name)
+            assert_exact(got, want, "%s: reduce" % L.name)
+        else:
+            err = np.abs(got - ph.sum(0))
+            assert (err <= gz * 2.0 ** -24 * np.abs(ph).sum(0) + 1e-30).all(), "reduce differs from the sum of the slices"
+
+
 def test_stem_deconv_is_reproducible_bit_for_bit(cks):
     """The few-channel input gradient composes its sums in a fixed order (no atomics)."""
     import torch
