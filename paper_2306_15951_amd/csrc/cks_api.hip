@@ -220,7 +220,9 @@ int launch_strip_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hi
     const long long tiles = (long long)g.N * Q.nBands * Q.nRowTiles;
     if (!fits_i31(tiles * Q.nT)) return CKS_ERR_SHAPE;
     Q.tiles = (int)tiles;
-    const int groups = Q.tiles < 2 * kCUs ? Q.tiles : 2 * kCUs;   // two workgroups per compute unit
+    int per_cu = 2;   // workgroups per compute unit
+    if (const char *t = getenv("CKS_TUNE_STRIP_FWD")) per_cu = atoi(t) > 0 ? atoi(t) : 2;   // tuning experiments only
+    const int groups = Q.tiles < per_cu * kCUs ? Q.tiles : per_cu * kCUs;
     Q.tilesPerBlock = (Q.tiles + groups - 1) / groups;
     const int blocks = ((Q.tiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
     return launch(strip_fwd<FH, FW, IC, S>, Q, blocks, SG::lds_bytes(), st, kStripThreads);
