@@ -168,6 +168,44 @@ def test_midsize_geometries(cks, oracle, geo):
     check_layer(cks, oracle, synth.Layer(*geo), seed=100 + [g[0] for g in MID].index(geo[0]))
 
 
+def random_geometries(count, seed):
+    """Valid layer geometries drawn at random (fixed seed): small enough for the full oracle, biased
+    towards the channel counts and filters that select the specialised kernels."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        C = int(rng.choice([1, 2, 3, 3, 3, 4, 5, 8, 12, 16, 20, 32, 36, 64, 96]))
+        OC = int(rng.choice([1, 3, 4, 8, 16, 20, 32, 32, 64, 64, 70, 96, 128]))
+        FH, FW = (int(rng.choice([1, 2, 3, 3, 3, 4, 5, 7, 7])) for _ in range(2))
+        if rng.random() < 0.6:
+            FW = FH
+        s = int(rng.choice([1, 1, 2, 2, 3]))
+        p = int(rng.integers(0, max(FH, FW) + 1))
+        H, W = int(rng.integers(1, 41)), int(rng.integers(1, 41))
+        if C <= 3 and rng.random() < 0.5:
+            W = int(rng.integers(40, 260))        # several bands of the few-channel kernels
+        N = int(rng.choice([1, 2, 3, 5, 16, 33, 64, 70]))
+        if H + 2 * p < FH or W + 2 * p < FW:
+            continue
+        OH, OW = (H + 2 * p - FH) // s + 1, (W + 2 * p - FW) // s + 1
+        macs = N * OH * OW * OC * FH * FW * C
+        if macs > 3e8 or N * H * W * C > 4e6 or N * OH * OW * OC > 4e6:
+            continue
+        out.append(("rand%02d" % len(out), N, C, H, W, OC, FH, FW, s, p))
+    return out
+
+
+RANDOM = random_geometries(48, 20230615)
+
+
+@pytest.mark.parametrize("geo", RANDOM, ids=[g[0] for g in RANDOM])
+def test_random_geometries(cks, oracle, geo):
+    from paper_2306_15951_amd import synth
+
+    print("geometry", geo, flush=True)
+    check_layer(cks, oracle, synth.Layer(*geo), seed=500 + int(geo[0][4:]), kinds=("int",))
+
+
 def structured_samples(shape, rng, n_random):
     """Random flat indices plus the corners / borders of every axis."""
     idx = [rng.integers(0, int(np.prod(shape)), size=n_random)]
