@@ -101,6 +101,17 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
     P.total = (int)total;
     P.bandBlocks = (int)bandBlocks;
+    P.dBand = make_fastdiv(P.bandBlocks);
+    P.dNT = make_fastdiv(P.nTiles);
+    P.dMT = make_fastdiv(P.mTiles);
+    P.dItemsW = make_fastdiv(P.itemsW);
+    P.dS = make_fastdiv(P.s);
+    P.pmods = P.p % P.s;
+    {
+        // output rows of a tile are one image apart
+        const long long rowO = OP == OP_FWD ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;
+        P.bufStore = rowO * BM * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_BUFFER_STORES");
+    }
     const size_t lds = rowrun_lds_bytes<BM, BN>();
     // Fast loads need: 16-byte vectors, every run a whole number of 32-float
     // chunks (the run is a multiple of the contracted channel count), and the

@@ -21,6 +21,29 @@ __device__ inline floatx16 mfma32(float a, float b, floatx16 c)
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
+// Division of a non-negative 31-bit number by a divisor fixed on the host: one multiply-high and a
+// shift.  The compiler's own expansion of a division by a kernel argument runs through the float
+// reciprocal on the vector ALU even for wave-uniform operands, and vector ALU time is MFMA time.
+// mul = ceil(2^(31 + ceil(log2 d)) / d), shr = ceil(log2 d) - 1  (d >= 2); exact for 0 <= x < 2^31.
+struct FastDiv {
+    int d;
+    unsigned mul, shr;
+};
+inline FastDiv make_fastdiv(int d)
+{
+    FastDiv f{d, 0u, 0u};
+    if (d > 1) {
+        unsigned lg = 0;
+        while ((1ll << lg) < d) ++lg;
+        const unsigned long long p2 = 1ull << (31 + lg);
+        f.mul = (unsigned)((p2 + (unsigned long long)d - 1) / (unsigned long long)d);
+        f.shr = lg - 1;
+    }
+    return f;
+}
+__device__ inline int fdiv(int x, const FastDiv &f) { return f.d == 1 ? x : (int)(__umulhi((unsigned)x, f.mul) >> f.shr); }
+__device__ inline int fmod(int x, const FastDiv &f) { return x - fdiv(x, f) * f.d; }
+
 // Workgroups are handed to the 8 dies round-robin.  Map the hardware block id
 // to a work item so that each die gets one contiguous range of work items;
 // neighbours in that order share operands and therefore that die's L2.

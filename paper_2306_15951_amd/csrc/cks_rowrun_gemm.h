@@ -48,6 +48,10 @@ struct RowRunParams {
     int mTiles, nTiles;
     int bandBlocks;       // workgroups per band = items per band * mTiles * nTiles
     int total;            // workgroups with work
+    // divisors of the work decoding, prepared on the host (see FastDiv)
+    FastDiv dBand, dNT, dMT, dItemsW, dS;
+    int pmods;            // p mod s
+    int bufStore;         // the tile's BM output rows span less than 2 GiB: stores go through a buffer descriptor
 };
 
 struct RunSet {
@@ -61,11 +65,13 @@ struct RunSet {
 // The a-th index of [0, I) when indices are listed class by class, class
 // y = (i + p) mod s, y = 0, 1, ...  (sub-kernel extents shrink with y, so the
 // classes with most work come first).
-__device__ inline int class_major_index(int a, int I, int s, int p)
+__device__ inline int class_major_index(int a, int I, const FastDiv &dS, int pmods)
 {
+    const int s = dS.d;
     for (int y = 0; y < s; ++y) {
-        int i0 = ((y - p) % s + s) % s;
-        int cnt = i0 < I ? (I - 1 - i0) / s + 1 : 0;
+        int i0 = y - pmods;   // first index of class y: (y - p) mod s
+        if (i0 < 0) i0 += s;
+        int cnt = i0 < I ? fdiv(I - 1 - i0, dS) + 1 : 0;
         if (a < cnt) return i0 + a * s;
         a -= cnt;
     }
@@ -100,10 +106,11 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         // Algorithm 2B: class (y,x) of (ih,iw), its sub-kernel extent CH x CW,
         // the window start (oh_s,ow_s) in dY and the trim [ch_s,ch_e) x [cw_s,cw_e).
         const int ih = ph, iw = pw;
-        int y = (ih + P.p) % P.s, x = (iw + P.p) % P.s;
-        int CH = y < P.FH ? (P.FH - y + P.s - 1) / P.s : 0;
-        int CW = x < P.FW ? (P.FW - x + P.s - 1) / P.s : 0;
-        int oh_s = (ih + P.p - y) / P.s - (CH - 1), ow_s = (iw + P.p - x) / P.s - (CW - 1);
+        const int qh = fdiv(ih + P.p, P.dS), qw = fdiv(iw + P.p, P.dS);
+        int y = ih + P.p - qh * P.s, x = iw + P.p - qw * P.s;
+        int CH = y < P.FH ? fdiv(P.FH - y + P.s - 1, P.dS) : 0;
+        int CW = x < P.FW ? fdiv(P.FW - x + P.s - 1, P.dS) : 0;
+        int oh_s = qh - (CH - 1), ow_s = qw - (CW - 1);
         int ch_s = max(-oh_s, 0), ch_e = min(P.OH - oh_s, CH);
         int cw_s = max(-ow_s, 0), cw_e = min(P.OW - ow_s, CW);
         R.nruns = max(ch_e - ch_s, 0);
@@ -134,12 +141,12 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 // bandBlocks consecutive workgroups (tiles of neighbouring items, which share
 // operands and so that die's L2); bands go to the dies in a serpentine order,
 // so every die gets the same mix of expensive interior and cheap border items.
-__device__ inline int banded_work(int bid, int bandBlocks)
+__device__ inline int banded_work(int bid, const FastDiv &dBand)
 {
     const int xcd = bid % kXcds, slot = bid / kXcds;
-    const int round = slot / bandBlocks;
+    const int round = fdiv(slot, dBand);
     const int band = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
-    return band * bandBlocks + slot % bandBlocks;
+    return band * dBand.d + (slot - round * dBand.d);
 }
 
 // Workgroup tile BM (batch rows) x BN (channels), K-chunk of 32 floats, LDS
@@ -177,17 +184,16 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     float *As = smem;                 // [2][BM][LDK]
     float *Bs = smem + 2 * BM * LDK;  // [2][BN][LDK]
 
-    const int work = banded_work(blockIdx.x, P.bandBlocks);
+    const int work = banded_work(blockIdx.x, P.dBand);
     if (work >= P.total) return;
-    const int nt = work % P.nTiles;
-    const int mt = (work / P.nTiles) % P.mTiles;
-    const int item = work / (P.nTiles * P.mTiles);
-    int ph = item / P.itemsW, pw = item % P.itemsW;
-    ph = (ph + P.rotH) % P.itemsH;
-    pw = (pw + P.rotW) % P.itemsW;
+    const int wq = fdiv(work, P.dNT), nt = work - wq * P.nTiles;
+    const int item = fdiv(wq, P.dMT), mt = wq - item * P.mTiles;
+    int ph = fdiv(item, P.dItemsW), pw = item - ph * P.itemsW;
+    ph += P.rotH; if (ph >= P.itemsH) ph -= P.itemsH;   // rotH < itemsH
+    pw += P.rotW; if (pw >= P.itemsW) pw -= P.itemsW;
     if (OP != OP_FWD) {
-        ph = class_major_index(ph, P.IH, P.s, P.p);
-        pw = class_major_index(pw, P.IW, P.s, P.p);
+        ph = class_major_index(ph, P.IH, P.dS, P.pmods);
+        pw = class_major_index(pw, P.IW, P.dS, P.pmods);
     }
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -226,14 +232,14 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     for (int i = 0; i < PB; ++i) {
         const int c = min(n0 + lr + 32 * i, R.NC - 1);
         pb[i] = P.B + (long)c * R.strideB + R.b0 + lc;
-        vb[i] = BK ? (unsigned)(((long)(brow + RPP * i) * R.strideB + bcol) * 4)
+        // BK: a column past the last input channel would be the next tap's (or, at the very end of the
+        // filter, past the allocation): it carries an offset beyond the buffer and reads as zero
+        vb[i] = BK ? (n0 + bcol < R.NC ? (unsigned)(((long)(brow + RPP * i) * R.strideB + bcol) * 4) : 0x80000000u)
                    : (unsigned)(((long)(c - n0) * R.strideB + lc) * 4);
     }
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(P.A + (long)min(m0, P.N - 1) * R.strideA + R.a0), 0, -1, 0x00020000);
-    // BK: the filter from column n0 on, as a buffer of its true size: columns past IC in the last
-    // filter row of all are out of range and read as zero (elsewhere they are the next tap's, and
-    // feed output columns that are never stored)
+    // BK: the filter from column n0 on, as a buffer of its true size
     const __amdgpu_buffer_rsrc_t rsB =
         BK ? __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + n0), 0,
                                                (int)(((long)P.OC * R.strideB - n0) * 4), 0x00020000)
@@ -356,6 +362,26 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
 
     // Every output element of the tile is stored, also when the trimmed range
     // was empty (then it is +0.0).  32 lanes write 128 contiguous bytes.
+    if (P.bufStore && m0 + BM <= P.N) {
+        // A full tile's rows as one raw buffer: lane part of the offset once, row part as a scalar
+        // offset (which the hardware does not range-check: hence full tiles only), no vector
+        // arithmetic per store.  A column past the channels carries an offset beyond the buffer.
+        const __amdgpu_buffer_rsrc_t rsO = __builtin_amdgcn_make_buffer_rsrc(
+            P.Out + (long)m0 * R.strideO, 0, (int)(BM * R.strideO * 4), 0x00020000);
+        const int so = (int)R.strideO * 4, o0b = (int)R.o0 * 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+                const int voff = col < R.NC ? ((wm * TM + i) * 32 + 4 * (lane >> 5)) * so + col * 4 : (int)0x80000000u;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][r]), rsO, voff,
+                                                          o0b + (8 * (r >> 2) + (r & 3)) * so, 0);
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
