@@ -362,6 +362,14 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
 {
     const size_t lds = pixel_lds_bytes<BM, BN, KC>();
     const int blocks = P.perXcd * kXcds;
+    P.dNT = make_fastdiv(P.nTiles);
+    P.dMT = make_fastdiv(P.mTiles);
+    P.dTaps = make_fastdiv(P.FH * P.FW);
+    P.dFW = make_fastdiv(P.FW);
+    P.dS = make_fastdiv(P.s);
+    P.dGZ = make_fastdiv(P.GZ);
+    P.dNC = make_fastdiv(P.N / KC > 0 ? P.N / KC : 1);
+    P.bufStore = P.sliceElems * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_BUFFER_STORES");
     // batch-inner ordering with scalar chunk offsets (see pixel_gemm_fast)
     const bool fast = veca && vecb && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
                       (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS");

@@ -28,6 +28,9 @@ struct PixelGemmParams {
     int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
     int GZ, mTiles, nTiles, total, perXcd;
     long sliceElems;  // OC*FH*FW*IC
+    // divisors of the work decoding, prepared on the host (see FastDiv)
+    FastDiv dNT, dMT, dTaps, dFW, dS, dGZ, dNC;   // nTiles, mTiles, FH*FW, FW, s, GZ, N/KC (chunks per pixel of pixel_gemm_fast)
+    int bufStore;     // a slice is below 2 GiB: full tiles are stored through a buffer descriptor
 };
 
 // Pixel counter inside a tap's trimmed range: k = (n*nOH + a)*nOW + b.
@@ -100,6 +103,25 @@ __device__ inline void wgrad_tile_epilogue(floatx16 (&acc)[TM][TN], float *smem,
         if (wk != 0) return;
     }
     float *out = P.Out + (long)z * P.sliceElems;
+    if (P.bufStore && m0 + WAVES_M * TM * 32 <= P.OC) {
+        // A tile with all its output channels: the slice as a raw buffer, lane part of the offset once,
+        // row part as a scalar offset (not range-checked by the hardware: hence full tiles only); an
+        // input channel past the end carries an offset beyond the buffer.  No vector arithmetic per store.
+        const __amdgpu_buffer_rsrc_t rsO = __builtin_amdgcn_make_buffer_rsrc(out, 0, (int)(P.sliceElems * 4), 0x00020000);
+        const int rowB = P.FH * P.FW * P.IC * 4;   // bytes between output channels
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int ic = n0 + (wn * TN + j) * 32 + (lane & 31);
+                const int oc0 = m0 + (wm * TM + i) * 32 + 4 * (lane >> 5);
+                const int voff = ic < P.IC ? oc0 * rowB + (tap * P.IC + ic) * 4 : (int)0x80000000u;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][r]), rsO, voff, (8 * (r >> 2) + (r & 3)) * rowB, 0);
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -295,21 +317,23 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_fast(const PixelGemmParam
 
     const int work = xcd_contiguous_work(blockIdx.x, P.perXcd);
     if (work >= P.total) return;
-    const int nt = work % P.nTiles;
-    const int mt = (work / P.nTiles) % P.mTiles;
-    const int tap = (work / (P.nTiles * P.mTiles)) % (P.FH * P.FW);
-    const int z = work / (P.nTiles * P.mTiles * P.FH * P.FW);
-    const int fh = tap / P.FW, fw = tap - fh * P.FW;
+    const int q1 = fdiv(work, P.dNT), nt = work - q1 * P.nTiles;
+    const int q2 = fdiv(q1, P.dMT), mt = q1 - q2 * P.mTiles;
+    const int z = fdiv(q2, P.dTaps), tap = q2 - z * P.dTaps.d;
+    const int fh = fdiv(tap, P.dFW), fw = tap - fh * P.FW;
     const int m0 = mt * BM, n0 = nt * BN;
 
-    // Algorithm 3B: the (oh,ow) whose X element exists for this tap.
+    // Algorithm 3B: the (oh,ow) whose X element exists for this tap.  ceil(a/s) for a of either sign
+    // (a > -(FH + FW)): shift the numerator by a multiple of s that makes it non-negative.
     const int ih_s = fh - P.p, iw_s = fw - P.p;
-    const int oh_s = max(cdiv_any(-ih_s, P.s), 0), oh_e = min(P.OH, cdiv_any(P.IH - ih_s, P.s));
-    const int ow_s = max(cdiv_any(-iw_s, P.s), 0), ow_e = min(P.OW, cdiv_any(P.IW - iw_s, P.s));
+    const int shiftK = P.FH + P.FW;
+    auto cdiv_s = [&](int a) { return fdiv(a + shiftK * P.s + P.s - 1, P.dS) - shiftK; };
+    const int oh_s = max(cdiv_s(-ih_s), 0), oh_e = min(P.OH, cdiv_s(P.IH - ih_s));
+    const int ow_s = max(cdiv_s(-iw_s), 0), ow_e = min(P.OW, cdiv_s(P.IW - iw_s));
     const int nOH = max(oh_e - oh_s, 0), nOW = max(ow_e - ow_s, 0);
-    const int NC = P.N / KC;                       // chunks per (oh,ow)
+    const int NC = P.dNC.d;                        // chunks per (oh,ow): N / KC
     const int Ct = nOH * nOW * NC;                 // chunks of this tap
-    const int seg = (Ct + P.GZ - 1) / P.GZ;
+    const int seg = fdiv(Ct + P.GZ - 1, P.dGZ);
     const int cbeg = min(z * seg, Ct), T = min(cbeg + seg, Ct) - cbeg;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -333,8 +357,8 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_fast(const PixelGemmParam
     // scalar part: position and first image of the chunk being loaded
     int nch = 0, pa_ = 0, pb_ = 0;
     if (T > 0) {
-        nch = cbeg % NC;
-        const int pos = cbeg / NC;
+        const int pos = fdiv(cbeg, P.dNC);
+        nch = cbeg - pos * NC;
         pa_ = pos / nOW;
         pb_ = pos - pa_ * nOW;
     }
