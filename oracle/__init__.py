@@ -41,7 +41,7 @@ def _load():
         fp = ctypes.POINTER(ctypes.c_float)
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int64)
-        geo = [ctypes.c_int] * 9
+        geo = [ctypes.c_int] * 11   # N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw
         for name in ("cko_conv_fwd", "cko_deconv", "cko_wgrad"):
             f = getattr(lib, name)
             f.argtypes = [fp, fp, dp] + geo + [ip, ctypes.c_int64]
@@ -50,7 +50,7 @@ def _load():
         lib.cko_brute.restype = ctypes.c_int
         lib.cko_filter_transpose.argtypes = [fp, fp] + [ctypes.c_int] * 4
         lib.cko_filter_transpose.restype = ctypes.c_int
-        lib.cko_kernel_split.argtypes = [fp, fp] + [ctypes.c_int] * 5
+        lib.cko_kernel_split.argtypes = [fp, fp] + [ctypes.c_int] * 6
         lib.cko_kernel_split.restype = ctypes.c_int
         lib.cko_mac_counts.argtypes = [ip] + geo
         lib.cko_mac_counts.restype = ctypes.c_int
@@ -84,6 +84,15 @@ def _sample(sample):
     return s, s.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), s.size
 
 
+def pair(v):
+    """Stride or padding as (vertical, horizontal): an int applies to both axes
+    (Table I writes them as <sh sw> and <ph pw>)."""
+    if isinstance(v, (tuple, list)):
+        a, b = v
+        return int(a), int(b)
+    return int(v), int(v)
+
+
 def out_dim(I, F, s, p):
     """floor((I + 2p - F)/s) + 1."""
     return _load().cko_out_dim(I, F, s, p)
@@ -102,10 +111,11 @@ def conv_fwd(X, W, stride, padding, sample=None):
     OC, FH, FW, _ = W.shape
     X = _f32(X, (N, IH, IW, IC)); W = _f32(W, (OC, FH, FW, IC))
     lib = _load()
-    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    (sh, sw), (ph, pw) = pair(stride), pair(padding)
+    OH, OW = out_dim(IH, FH, sh, ph), out_dim(IW, FW, sw, pw)
     s, sp, ns = _sample(sample)
     out = np.empty(ns if s is not None else (N, OH, OW, OC), dtype=np.float64)
-    _check(lib.cko_conv_fwd(_fptr(X), _fptr(W), _dptr(out), N, IC, IH, IW, OC, FH, FW, stride, padding, sp, ns))
+    _check(lib.cko_conv_fwd(_fptr(X), _fptr(W), _dptr(out), N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw, sp, ns))
     return out
 
 
@@ -113,12 +123,13 @@ def deconv(dY, W, IH, IW, stride, padding, sample=None):
     """Eq. (2): dX[N,IH,IW,IC] (float64) from dY[N,OH,OW,OC], W[OC,FH,FW,IC]."""
     OC, FH, FW, IC = W.shape
     N = dY.shape[0]
-    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    (sh, sw), (ph, pw) = pair(stride), pair(padding)
+    OH, OW = out_dim(IH, FH, sh, ph), out_dim(IW, FW, sw, pw)
     dY = _f32(dY, (N, OH, OW, OC)); W = _f32(W, (OC, FH, FW, IC))
     lib = _load()
     s, sp, ns = _sample(sample)
     out = np.empty(ns if s is not None else (N, IH, IW, IC), dtype=np.float64)
-    _check(lib.cko_deconv(_fptr(dY), _fptr(W), _dptr(out), N, IC, IH, IW, OC, FH, FW, stride, padding, sp, ns))
+    _check(lib.cko_deconv(_fptr(dY), _fptr(W), _dptr(out), N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw, sp, ns))
     return out
 
 
@@ -126,12 +137,13 @@ def wgrad(X, dY, FH, FW, stride, padding, sample=None):
     """Eq. (3): dW[OC,FH,FW,IC] (float64) from X[N,IH,IW,IC], dY[N,OH,OW,OC]."""
     N, IH, IW, IC = X.shape
     OC = dY.shape[3]
-    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    (sh, sw), (ph, pw) = pair(stride), pair(padding)
+    OH, OW = out_dim(IH, FH, sh, ph), out_dim(IW, FW, sw, pw)
     X = _f32(X, (N, IH, IW, IC)); dY = _f32(dY, (N, OH, OW, OC))
     lib = _load()
     s, sp, ns = _sample(sample)
     out = np.empty(ns if s is not None else (OC, FH, FW, IC), dtype=np.float64)
-    _check(lib.cko_wgrad(_fptr(X), _fptr(dY), _dptr(out), N, IC, IH, IW, OC, FH, FW, stride, padding, sp, ns))
+    _check(lib.cko_wgrad(_fptr(X), _fptr(dY), _dptr(out), N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw, sp, ns))
     return out
 
 
@@ -139,11 +151,12 @@ def brute(X, W, dY, stride, padding):
     """7-deep scatter loop; returns (Y, dX, dW) as float64.  Tiny inputs only."""
     N, IH, IW, IC = X.shape
     OC, FH, FW, _ = W.shape
-    OH, OW = out_dim(IH, FH, stride, padding), out_dim(IW, FW, stride, padding)
+    (sh, sw), (ph, pw) = pair(stride), pair(padding)
+    OH, OW = out_dim(IH, FH, sh, ph), out_dim(IW, FW, sw, pw)
     X = _f32(X, (N, IH, IW, IC)); W = _f32(W, (OC, FH, FW, IC)); dY = _f32(dY, (N, OH, OW, OC))
     Y = np.empty((N, OH, OW, OC)); dX = np.empty((N, IH, IW, IC)); dW = np.empty((OC, FH, FW, IC))
     _check(_load().cko_brute(_fptr(X), _fptr(W), _fptr(dY), _dptr(Y), _dptr(dX), _dptr(dW),
-                             N, IC, IH, IW, OC, FH, FW, stride, padding))
+                             N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw))
     return Y, dX, dW
 
 
@@ -157,20 +170,21 @@ def filter_transpose(W):
 
 
 def kernel_split(W, stride):
-    """Algorithm 2 Stage 1 in the paper's layout C[s,s,OC,ceil(FH/s),ceil(FW/s),IC] (float32)."""
+    """Algorithm 2 Stage 1 in the paper's layout C[sh,sw,OC,ceil(FH/sh),ceil(FW/sw),IC] (float32)."""
     OC, FH, FW, IC = W.shape
     W = _f32(W, (OC, FH, FW, IC))
-    s = stride
-    out = np.empty((s, s, OC, -(-FH // s), -(-FW // s), IC), dtype=np.float32)
-    _check(_load().cko_kernel_split(_fptr(W), _fptr(out), OC, FH, FW, IC, s))
+    sh, sw = pair(stride)
+    out = np.empty((sh, sw, OC, -(-FH // sh), -(-FW // sw), IC), dtype=np.float32)
+    _check(_load().cko_kernel_split(_fptr(W), _fptr(out), OC, FH, FW, IC, sh, sw))
     return out
 
 
 def mac_counts(N, IC, IH, IW, OC, FH, FW, stride, padding):
     """dict(dense, useful, nominal_deconv, nominal_dilated) in multiply-adds, by enumeration."""
     c = np.zeros(4, dtype=np.int64)
+    (sh, sw), (ph, pw) = pair(stride), pair(padding)
     _check(_load().cko_mac_counts(c.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
-                                  N, IC, IH, IW, OC, FH, FW, stride, padding))
+                                  N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw))
     return dict(dense=int(c[0]), useful=int(c[1]), nominal_deconv=int(c[2]), nominal_dilated=int(c[3]))
 
 

@@ -27,6 +27,13 @@ def _cdiv(a, b):
     return -((-a) // b)
 
 
+def _pair(v):
+    """<sh sw> / <ph pw> of Table I; an int applies to both axes."""
+    if isinstance(v, (tuple, list)):
+        return int(v[0]), int(v[1])
+    return int(v), int(v)
+
+
 def _out_dim(I, F, s, p):
     return (I + 2 * p - F) // s + 1
 
@@ -36,14 +43,15 @@ def conv_v2(X, W, s, p):
     [fh_s, fh_e) x [fw_s, fw_e), the part that lies over real input."""
     N, IH, IW, IC = X.shape
     OC, FH, FW, _ = W.shape
-    OH, OW = _out_dim(IH, FH, s, p), _out_dim(IW, FW, s, p)
+    (sh, sw), (ph, pw) = _pair(s), _pair(p)
+    OH, OW = _out_dim(IH, FH, sh, ph), _out_dim(IW, FW, sw, pw)
     Y = np.zeros((N, OH, OW, OC))
     macs = 0
     Xd, Wd = X.astype(np.float64), W.astype(np.float64)
     for n in range(N):
         for oh in range(OH):
             for ow in range(OW):
-                ih_s, iw_s = oh * s - p, ow * s - p
+                ih_s, iw_s = oh * sh - ph, ow * sw - pw
                 fh_s, fh_e = max(-ih_s, 0), min(IH - ih_s, FH)
                 fw_s, fw_e = max(-iw_s, 0), min(IW - iw_s, FW)
                 for oc in range(OC):
@@ -65,32 +73,33 @@ def subkernel_extent(F, y, s):
 def ks_deconv(dY, C, IH, IW, FH, FW, s, p, trim):
     """Algorithm 2 Stage 2&3 (trim=False) / Algorithm 2B (trim=True).
 
-    ``C`` is the Stage-1 tensor in the paper's layout [s,s,OC,CHp,CWp,IC].
-    Class (y,x) owns the dX elements with (ih+p) mod s == y, (iw+p) mod s == x.
+    ``C`` is the Stage-1 tensor in the paper's layout [sh,sw,OC,CHp,CWp,IC].
+    Class (y,x) owns the dX elements with (ih+ph) mod sh == y, (iw+pw) mod sw == x.
     Also returns how often each dX element was written (must be exactly once)."""
     N, OH, OW, OC = dY.shape
     IC = C.shape[5]
+    (sh, sw), (ph, pw) = _pair(s), _pair(p)
     dX = np.full((N, IH, IW, IC), np.nan)
     writes = np.zeros((IH, IW), dtype=np.int64)
     macs = 0
     dYd, Cd = dY.astype(np.float64), C.astype(np.float64)
-    for y in range(s):
-        for x in range(s):
-            CH, CW = subkernel_extent(FH, y, s), subkernel_extent(FW, x, s)
+    for y in range(sh):
+        for x in range(sw):
+            CH, CW = subkernel_extent(FH, y, sh), subkernel_extent(FW, x, sw)
             oph, opw = CH - 1, CW - 1
-            ih_s, iw_s = y - p, x - p
+            ih_s, iw_s = y - ph, x - pw
             if ih_s < 0:
-                ih_s += _cdiv(-ih_s, s) * s
+                ih_s += _cdiv(-ih_s, sh) * sh
             if iw_s < 0:
-                iw_s += _cdiv(-iw_s, s) * s
-            for u in range(_cdiv(IH, s)):
-                for v in range(_cdiv(IW, s)):
-                    ih, iw = u * s + ih_s, v * s + iw_s
+                iw_s += _cdiv(-iw_s, sw) * sw
+            for u in range(_cdiv(IH, sh)):
+                for v in range(_cdiv(IW, sw)):
+                    ih, iw = u * sh + ih_s, v * sw + iw_s
                     if not (0 <= ih < IH and 0 <= iw < IW):
                         continue
-                    assert (ih + p - y) % s == 0 and (iw + p - x) % s == 0
-                    oh_s = (ih + p - y) // s - oph
-                    ow_s = (iw + p - x) // s - opw
+                    assert (ih + ph - y) % sh == 0 and (iw + pw - x) % sw == 0
+                    oh_s = (ih + ph - y) // sh - oph
+                    ow_s = (iw + pw - x) // sw - opw
                     if trim:
                         ch_s, ch_e = max(-oh_s, 0), min(OH - oh_s, CH)
                         cw_s, cw_e = max(-ow_s, 0), min(OW - ow_s, CW)
@@ -115,18 +124,19 @@ def ks_deconv(dY, C, IH, IW, FH, FW, s, p, trim):
 
 def sk_dilated(X, dY, FH, FW, s, p, trim):
     """Algorithm 3 (trim=False) / Algorithm 3B (trim=True): dY is used as it is,
-    X is read with a leaping step s."""
+    X is read with a leaping step (sh, sw)."""
     N, IH, IW, IC = X.shape
     _, OH, OW, OC = dY.shape
+    (sh, sw), (ph, pw) = _pair(s), _pair(p)
     dW = np.zeros((OC, FH, FW, IC))
     macs = 0
     Xd, dYd = X.astype(np.float64), dY.astype(np.float64)
     for fh in range(FH):
         for fw in range(FW):
-            ih_s, iw_s = fh - p, fw - p
+            ih_s, iw_s = fh - ph, fw - pw
             if trim:
-                oh_s, oh_e = max(_cdiv(-ih_s, s), 0), min(OH, _cdiv(IH - ih_s, s))
-                ow_s, ow_e = max(_cdiv(-iw_s, s), 0), min(OW, _cdiv(IW - iw_s, s))
+                oh_s, oh_e = max(_cdiv(-ih_s, sh), 0), min(OH, _cdiv(IH - ih_s, sh))
+                ow_s, ow_e = max(_cdiv(-iw_s, sw), 0), min(OW, _cdiv(IW - iw_s, sw))
             else:
                 oh_s, oh_e, ow_s, ow_e = 0, OH, 0, OW
             for oc in range(OC):
@@ -135,7 +145,7 @@ def sk_dilated(X, dY, FH, FW, s, p, trim):
                     for n in range(N):
                         for oh in range(oh_s, oh_e):
                             for ow in range(ow_s, ow_e):
-                                ih, iw = oh * s + ih_s, ow * s + iw_s
+                                ih, iw = oh * sh + ih_s, ow * sw + iw_s
                                 if not trim and not (0 <= ih < IH and 0 <= iw < IW):
                                     macs += 1  # Alg. 3 as printed skips these; Fig. 7 counts them
                                     continue

@@ -11,9 +11,13 @@
  *   X  [N][IH][IW][IC]    input feature maps            (float)
  *   W  [OC][FH][FW][IC]   filters                       (float)
  *   Y  [N][OH][OW][OC]    output feature maps
- *   OH = floor((IH + 2p - FH) / s) + 1, likewise OW     (the paper never
- *        writes this down; it is the only reading that fits Table III and
- *        the worked example of Fig. 1/4)
+ *   OH = floor((IH + 2 ph - FH) / sh) + 1, OW likewise with pw, sw  (the
+ *        paper never writes this down; it is the only reading that fits
+ *        Table III and the worked example of Fig. 1/4)
+ *
+ * Stride and padding are given per axis, <sh sw> and <ph pw> of Table I; the
+ * paper's algorithms are printed with both and its examples use sh = sw,
+ * ph = pw.
  *
  *   Eq. (1)  Y  = conv2D(X, W)              zero padding made explicit
  *   Eq. (2)  dX = deconv2D(dY, rot180(W))   zero insertion made explicit
@@ -35,7 +39,7 @@
  *
  * Pins (see tests): a 7-deep brute-force scatter loop (cko_brute, below, which
  * shares nothing with the three operators but the index relation
- * ih = oh*s - p + fh), an independent library convolution, the adjoint
+ * ih = oh*sh - ph + fh), an independent library convolution, the adjoint
  * identities, finite differences, closed forms and the paper's worked example.
  */
 #include <stdint.h>
@@ -64,38 +68,40 @@ static int out_dim(int I, int F, int s, int p)
 
 int cko_out_dim(int I, int F, int s, int p) { return out_dim(I, F, s, p); }
 
-static int bad_geometry(int N, int IC, int IH, int IW, int OC, int FH, int FW, int s, int p)
+static int bad_geometry(int N, int IC, int IH, int IW, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
 {
     if (N <= 0 || IC <= 0 || IH <= 0 || IW <= 0 || OC <= 0 || FH <= 0 || FW <= 0) return 1;
-    if (s < 1 || p < 0) return 1;
-    if (IH + 2 * p < FH || IW + 2 * p < FW) return 1;
+    if (sh < 1 || sw < 1 || ph < 0 || pw < 0) return 1;
+    if (IH + 2 * ph < FH || IW + 2 * pw < FW) return 1;
     return 0;
 }
 
-/* X with an explicit border of p zeros on every side: [N][IH+2p][IW+2p][IC]. */
-static float *make_padded(const float *X, int N, int IH, int IW, int IC, int p)
+/* X with an explicit border of zeros, ph rows above and below, pw columns left
+ * and right: [N][IH+2ph][IW+2pw][IC]. */
+static float *make_padded(const float *X, int N, int IH, int IW, int IC, int ph, int pw)
 {
-    size_t PH = (size_t)IH + 2 * p, PW = (size_t)IW + 2 * p;
+    size_t PH = (size_t)IH + 2 * ph, PW = (size_t)IW + 2 * pw;
     float *Xp = (float *)calloc((size_t)N * PH * PW * IC, sizeof(float));
     if (!Xp) return NULL;
     for (int n = 0; n < N; ++n)
         for (int ih = 0; ih < IH; ++ih)
-            memcpy(Xp + (((size_t)n * PH + ih + p) * PW + p) * IC,
+            memcpy(Xp + (((size_t)n * PH + ih + ph) * PW + pw) * IC,
                    X + (((size_t)n * IH + ih) * IW) * IC, (size_t)IW * IC * sizeof(float));
     return Xp;
 }
 
-/* dY with (s-1) explicit zeros between neighbours: [N][(OH-1)s+1][(OW-1)s+1][OC]
+/* dY with (sh-1) / (sw-1) explicit zeros between vertical / horizontal
+ * neighbours: [N][(OH-1)sh+1][(OW-1)sw+1][OC]
  * (Section III, second paragraph on backward propagation; Table III, O^p). */
-static float *make_dilated(const float *dY, int N, int OH, int OW, int OC, int s)
+static float *make_dilated(const float *dY, int N, int OH, int OW, int OC, int sh, int sw)
 {
-    size_t DH = (size_t)(OH - 1) * s + 1, DW = (size_t)(OW - 1) * s + 1;
+    size_t DH = (size_t)(OH - 1) * sh + 1, DW = (size_t)(OW - 1) * sw + 1;
     float *D = (float *)calloc((size_t)N * DH * DW * OC, sizeof(float));
     if (!D) return NULL;
     for (int n = 0; n < N; ++n)
         for (int oh = 0; oh < OH; ++oh)
             for (int ow = 0; ow < OW; ++ow)
-                memcpy(D + (((size_t)n * DH + (size_t)oh * s) * DW + (size_t)ow * s) * OC,
+                memcpy(D + (((size_t)n * DH + (size_t)oh * sh) * DW + (size_t)ow * sw) * OC,
                        dY + (((size_t)n * OH + oh) * OW + ow) * OC, (size_t)OC * sizeof(float));
     return D;
 }
@@ -103,13 +109,13 @@ static float *make_dilated(const float *dY, int N, int OH, int OW, int OC, int s
 /* ------------------------------------------------------------------ Eq. (1) */
 
 int cko_conv_fwd(const float *X, const float *W, double *Y,
-                 int N, int IC, int IH, int IW, int OC, int FH, int FW, int s, int p,
+                 int N, int IC, int IH, int IW, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                  const int64_t *sample, int64_t nsample)
 {
-    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, s, p)) return -2;
-    const int OH = out_dim(IH, FH, s, p), OW = out_dim(IW, FW, s, p);
-    const size_t PH = (size_t)IH + 2 * p, PW = (size_t)IW + 2 * p;
-    float *Xp = make_padded(X, N, IH, IW, IC, p);
+    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw)) return -2;
+    const int OH = out_dim(IH, FH, sh, ph), OW = out_dim(IW, FW, sw, pw);
+    const size_t PH = (size_t)IH + 2 * ph, PW = (size_t)IW + 2 * pw;
+    float *Xp = make_padded(X, N, IH, IW, IC, ph, pw);
     if (!Xp) return -9;
     const int64_t total = sample ? nsample : (int64_t)N * OH * OW * OC;
 #pragma omp parallel for schedule(static)
@@ -122,7 +128,7 @@ int cko_conv_fwd(const float *X, const float *W, double *Y,
         double acc = 0.0;
         for (int fh = 0; fh < FH; ++fh)
             for (int fw = 0; fw < FW; ++fw) {
-                const float *xr = Xp + (((size_t)n * PH + (size_t)oh * s + fh) * PW + (size_t)ow * s + fw) * IC;
+                const float *xr = Xp + (((size_t)n * PH + (size_t)oh * sh + fh) * PW + (size_t)ow * sw + fw) * IC;
                 const float *wr = W + (((size_t)oc * FH + fh) * FW + fw) * IC;
                 for (int ic = 0; ic < IC; ++ic) acc += (double)xr[ic] * (double)wr[ic];
             }
@@ -135,14 +141,14 @@ int cko_conv_fwd(const float *X, const float *W, double *Y,
 /* ------------------------------------------------------------------ Eq. (2) */
 
 int cko_deconv(const float *dY, const float *W, double *dX,
-               int N, int IC, int IH, int IW, int OC, int FH, int FW, int s, int p,
+               int N, int IC, int IH, int IW, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                const int64_t *sample, int64_t nsample)
 {
-    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, s, p)) return -2;
-    const int OH = out_dim(IH, FH, s, p), OW = out_dim(IW, FW, s, p);
+    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw)) return -2;
+    const int OH = out_dim(IH, FH, sh, ph), OW = out_dim(IW, FW, sw, pw);
     /* Canvas: the zero-inserted gradient laid on zeros so that a unit-stride
      * correlation with the rotated filter yields exactly IH x IW outputs.
-     * Cell (oh*s + FH-1-p, ow*s + FW-1-p) holds dY[oh][ow]; cells that would
+     * Cell (oh*sh + FH-1-ph, ow*sw + FW-1-pw) holds dY[oh][ow]; cells that would
      * fall outside are ones no dX element can see, and are dropped. */
     const size_t CH = (size_t)IH + FH - 1, CW = (size_t)IW + FW - 1;
     float *Z = (float *)calloc((size_t)N * CH * CW * OC, sizeof(float));
@@ -151,7 +157,7 @@ int cko_deconv(const float *dY, const float *W, double *dX,
     for (int n = 0; n < N; ++n)
         for (int oh = 0; oh < OH; ++oh)
             for (int ow = 0; ow < OW; ++ow) {
-                long th = (long)oh * s + FH - 1 - p, tw = (long)ow * s + FW - 1 - p;
+                long th = (long)oh * sh + FH - 1 - ph, tw = (long)ow * sw + FW - 1 - pw;
                 if (th < 0 || tw < 0 || th >= (long)CH || tw >= (long)CW) continue;
                 memcpy(Z + (((size_t)n * CH + th) * CW + tw) * OC,
                        dY + (((size_t)n * OH + oh) * OW + ow) * OC, (size_t)OC * sizeof(float));
@@ -188,15 +194,15 @@ int cko_deconv(const float *dY, const float *W, double *dX,
 /* ------------------------------------------------------------------ Eq. (3) */
 
 int cko_wgrad(const float *X, const float *dY, double *dW,
-              int N, int IC, int IH, int IW, int OC, int FH, int FW, int s, int p,
+              int N, int IC, int IH, int IW, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
               const int64_t *sample, int64_t nsample)
 {
-    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, s, p)) return -2;
-    const int OH = out_dim(IH, FH, s, p), OW = out_dim(IW, FW, s, p);
-    const size_t PH = (size_t)IH + 2 * p, PW = (size_t)IW + 2 * p;
-    const size_t DH = (size_t)(OH - 1) * s + 1, DW = (size_t)(OW - 1) * s + 1;
-    float *Xp = make_padded(X, N, IH, IW, IC, p);
-    float *D = make_dilated(dY, N, OH, OW, OC, s);
+    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw)) return -2;
+    const int OH = out_dim(IH, FH, sh, ph), OW = out_dim(IW, FW, sw, pw);
+    const size_t PH = (size_t)IH + 2 * ph, PW = (size_t)IW + 2 * pw;
+    const size_t DH = (size_t)(OH - 1) * sh + 1, DW = (size_t)(OW - 1) * sw + 1;
+    float *Xp = make_padded(X, N, IH, IW, IC, ph, pw);
+    float *D = make_dilated(dY, N, OH, OW, OC, sh, sw);
     if (!Xp || !D) { free(Xp); free(D); return -9; }
     const int64_t total = sample ? nsample : (int64_t)OC * FH * FW * IC;
 #pragma omp parallel for schedule(static)
@@ -225,10 +231,10 @@ int cko_wgrad(const float *X, const float *dY, double *dW,
  * dilation or rotation is ever formed; small inputs only (serial). */
 int cko_brute(const float *X, const float *W, const float *dY,
               double *Y, double *dX, double *dW,
-              int N, int IC, int IH, int IW, int OC, int FH, int FW, int s, int p)
+              int N, int IC, int IH, int IW, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
 {
-    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, s, p)) return -2;
-    const int OH = out_dim(IH, FH, s, p), OW = out_dim(IW, FW, s, p);
+    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw)) return -2;
+    const int OH = out_dim(IH, FH, sh, ph), OW = out_dim(IW, FW, sw, pw);
     memset(Y, 0, sizeof(double) * (size_t)N * OH * OW * OC);
     memset(dX, 0, sizeof(double) * (size_t)N * IH * IW * IC);
     memset(dW, 0, sizeof(double) * (size_t)OC * FH * FW * IC);
@@ -239,7 +245,7 @@ int cko_brute(const float *X, const float *W, const float *dY,
     for (int fh = 0; fh < FH; ++fh)
     for (int fw = 0; fw < FW; ++fw)
     for (int ic = 0; ic < IC; ++ic) {
-        int ih = oh * s - p + fh, iw = ow * s - p + fw;
+        int ih = oh * sh - ph + fh, iw = ow * sw - pw + fw;
         if (ih < 0 || ih >= IH || iw < 0 || iw >= IW) continue;
         size_t xi = (((size_t)n * IH + ih) * IW + iw) * IC + ic;
         size_t wi = (((size_t)oc * FH + fh) * FW + fw) * IC + ic;
@@ -269,28 +275,29 @@ int cko_filter_transpose(const float *W, float *Wt, int OC, int FH, int FW, int 
 static int cdiv_pos(int a, int b) { return (a + b - 1) / b; } /* a >= 0, b > 0 */
 
 /* Kernel split, Section IV.B Stage 1 and Algorithm 2 (Stage 1), in the paper's
- * own 6-D layout  C[s][s][OC][ceil(FH/s)][ceil(FW/s)][IC], zero-initialised.
- * Sub-kernel (y,x) has ceil((FH-y)/s) x ceil((FW-x)/s) taps (none if that is
- * <= 0, which happens when s > F); tap (ch,cw) of it is the filter tap
- *   fh = y + (oph - ch)*s,  fw = x + (opw - cw)*s,   oph = CH_y - 1,
- * i.e. the rotated filter sampled with step s.  Entries outside stay zero. */
-int cko_kernel_split(const float *W, float *Cs, int OC, int FH, int FW, int IC, int s)
+ * own 6-D layout  C[sh][sw][OC][ceil(FH/sh)][ceil(FW/sw)][IC], zero-initialised.
+ * Sub-kernel (y,x) has ceil((FH-y)/sh) x ceil((FW-x)/sw) taps (none if that is
+ * <= 0, which happens when a stride exceeds the filter); tap (ch,cw) of it is
+ * the filter tap
+ *   fh = y + (oph - ch)*sh,  fw = x + (opw - cw)*sw,   oph = CH_y - 1,
+ * i.e. the rotated filter sampled with steps sh, sw.  Entries outside stay zero. */
+int cko_kernel_split(const float *W, float *Cs, int OC, int FH, int FW, int IC, int sh, int sw)
 {
-    if (OC <= 0 || FH <= 0 || FW <= 0 || IC <= 0 || s < 1) return -2;
-    const int CHp = cdiv_pos(FH, s), CWp = cdiv_pos(FW, s);
-    memset(Cs, 0, sizeof(float) * (size_t)s * s * OC * CHp * CWp * IC);
-    for (int y = 0; y < s; ++y)
-        for (int x = 0; x < s; ++x) {
-            int CHy = y < FH ? cdiv_pos(FH - y, s) : 0;
-            int CWx = x < FW ? cdiv_pos(FW - x, s) : 0;
+    if (OC <= 0 || FH <= 0 || FW <= 0 || IC <= 0 || sh < 1 || sw < 1) return -2;
+    const int CHp = cdiv_pos(FH, sh), CWp = cdiv_pos(FW, sw);
+    memset(Cs, 0, sizeof(float) * (size_t)sh * sw * OC * CHp * CWp * IC);
+    for (int y = 0; y < sh; ++y)
+        for (int x = 0; x < sw; ++x) {
+            int CHy = y < FH ? cdiv_pos(FH - y, sh) : 0;
+            int CWx = x < FW ? cdiv_pos(FW - x, sw) : 0;
             int oph = CHy - 1, opw = CWx - 1;
             for (int oc = 0; oc < OC; ++oc)
                 for (int ch = 0; ch < CHy; ++ch)
                     for (int cw = 0; cw < CWx; ++cw) {
-                        int fh = y + (oph - ch) * s, fw = x + (opw - cw) * s;
+                        int fh = y + (oph - ch) * sh, fw = x + (opw - cw) * sw;
                         if (fh < 0 || fh >= FH || fw < 0 || fw >= FW) continue;
                         for (int ic = 0; ic < IC; ++ic)
-                            Cs[(((((size_t)y * s + x) * OC + oc) * CHp + ch) * CWp + cw) * IC + ic] =
+                            Cs[(((((size_t)y * sw + x) * OC + oc) * CHp + ch) * CWp + cw) * IC + ic] =
                                 W[(((size_t)oc * FH + fh) * FW + fw) * IC + ic];
                     }
         }
@@ -306,16 +313,16 @@ int cko_kernel_split(const float *W, float *Cs, int OC, int FH, int FW, int IC, 
  * counts[3] nominal MACs of the dilating filter gradient (T_Dilated / 2, with
  *           the batch factor N that the printed formula leaves out)
  * Counted by enumeration, not by formula, so the tests can pin the formulas. */
-int cko_mac_counts(int64_t *counts, int N, int IC, int IH, int IW, int OC, int FH, int FW, int s, int p)
+int cko_mac_counts(int64_t *counts, int N, int IC, int IH, int IW, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
 {
-    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, s, p)) return -2;
-    const int OH = out_dim(IH, FH, s, p), OW = out_dim(IW, FW, s, p);
+    if (bad_geometry(N, IC, IH, IW, OC, FH, FW, sh, sw, ph, pw)) return -2;
+    const int OH = out_dim(IH, FH, sh, ph), OW = out_dim(IW, FW, sw, pw);
     int64_t dense = 0, useful = 0;
     for (int oh = 0; oh < OH; ++oh)
         for (int ow = 0; ow < OW; ++ow)
             for (int fh = 0; fh < FH; ++fh)
                 for (int fw = 0; fw < FW; ++fw) {
-                    int ih = oh * s - p + fh, iw = ow * s - p + fw;
+                    int ih = oh * sh - ph + fh, iw = ow * sw - pw + fw;
                     ++dense;
                     if (ih >= 0 && ih < IH && iw >= 0 && iw < IW) ++useful;
                 }
@@ -323,6 +330,6 @@ int cko_mac_counts(int64_t *counts, int N, int IC, int IH, int IW, int OC, int F
     counts[0] = dense * ch;
     counts[1] = useful * ch;
     counts[2] = (int64_t)IH * IW * FH * FW * ch;
-    counts[3] = (int64_t)((OH - 1) * s + 1) * ((OW - 1) * s + 1) * FH * FW * ch;
+    counts[3] = (int64_t)((OH - 1) * sh + 1) * ((OW - 1) * sw + 1) * FH * FW * ch;
     return 0;
 }

@@ -327,6 +327,122 @@ def test_kernel_split_is_a_rotated_partition_of_the_filter(oracle):
                 assert np.all(C[y, x][:, mask] == 0)
 
 
+# ---------------------------------------------------------------- per-axis stride and padding
+# Table I writes stride and padding as <sh sw> and <ph pw>.  The same pins, on geometries whose two
+# axes differ in everything: a mistake that swaps the axes anywhere fails them.
+
+def asym_sweep():
+    """(N, IC, IH, IW, OC, FH, FW, (sh, sw), (ph, pw)) with sh != sw or ph != pw."""
+    out = []
+    for (IH, IW), (FH, FW), st, pd in itertools.product(
+        [(5, 8), (7, 4), (6, 6)], [(3, 3), (2, 3), (4, 1), (5, 2)],
+        [(1, 2), (2, 1), (2, 3), (3, 1), (4, 2)], [(0, 1), (1, 0), (2, 1), (1, 3), (0, 0), (3, 3)]
+    ):
+        if st[0] == st[1] and pd[0] == pd[1]:
+            continue
+        if IH + 2 * pd[0] < FH or IW + 2 * pd[1] < FW:
+            continue
+        out.append((2, 3, IH, IW, 2, FH, FW, st, pd))
+    return out
+
+
+ASYM = asym_sweep()
+
+
+def make_asym(g, seed, integer=True):
+    N, IC, IH, IW, OC, FH, FW, (sh, sw), (ph, pw) = g
+    OH, OW = (IH + 2 * ph - FH) // sh + 1, (IW + 2 * pw - FW) // sw + 1
+    rng = np.random.default_rng(seed)
+    shapes = ((N, IH, IW, IC), (OC, FH, FW, IC), (N, OH, OW, OC))
+    if integer:
+        return tuple(rand_int(rng, sh_) for sh_ in shapes)
+    return tuple(rng.standard_normal(sh_).astype(np.float32) for sh_ in shapes)
+
+
+def test_asymmetric_sweep_is_wide():
+    assert len(ASYM) > 250
+    assert any(g[7][0] > g[5] or g[7][1] > g[6] for g in ASYM)      # a stride larger than the filter
+    assert any((g[2] + 2 * g[8][0] - g[5]) % g[7][0] for g in ASYM)   # remainder rows
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_asymmetric_brute_force_equals_oracle_exactly(oracle, chunk):
+    for i, g in enumerate(ASYM[chunk::4]):
+        X, W, dY = make_asym(g, 7000 + i)
+        N, IC, IH, IW, OC, FH, FW, st, pd = g
+        Yb, dXb, dWb = oracle.brute(X, W, dY, st, pd)
+        assert np.array_equal(oracle.conv_fwd(X, W, st, pd), Yb), g
+        assert np.array_equal(oracle.deconv(dY, W, IH, IW, st, pd), dXb), g
+        assert np.array_equal(oracle.wgrad(X, dY, FH, FW, st, pd), dWb), g
+
+
+def test_asymmetric_against_library_convolution(oracle):
+    torch = pytest.importorskip("torch")
+    for i, g in enumerate(ASYM[::7]):
+        N, IC, IH, IW, OC, FH, FW, st, pd = g
+        X, W, dY = make_asym(g, 8000 + i, integer=False)
+        xt = torch.from_numpy(X.astype(np.float64)).permute(0, 3, 1, 2).clone().requires_grad_(True)
+        wt = torch.from_numpy(W.astype(np.float64)).permute(0, 3, 1, 2).clone().requires_grad_(True)
+        yt = torch.nn.functional.conv2d(xt, wt, stride=st, padding=pd)
+        yt.backward(torch.from_numpy(dY.astype(np.float64)).permute(0, 3, 1, 2))
+        np.testing.assert_allclose(oracle.conv_fwd(X, W, st, pd), yt.detach().permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(oracle.deconv(dY, W, IH, IW, st, pd), xt.grad.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(oracle.wgrad(X, dY, FH, FW, st, pd), wt.grad.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
+
+
+def test_asymmetric_all_ones_counts_the_real_taps(oracle):
+    """With X = W = 1 an output is IC times the number of its taps over real input: per axis the
+    trimmed range of Algorithm 1 with that axis' own stride and padding."""
+    N, IC, IH, IW, OC, FH, FW, (sh, sw), (ph, pw) = 1, 3, 7, 9, 2, 4, 3, (3, 2), (2, 1)
+    Y = oracle.conv_fwd(np.ones((N, IH, IW, IC), np.float32), np.ones((OC, FH, FW, IC), np.float32), (sh, sw), (ph, pw))
+    OH, OW = (IH + 2 * ph - FH) // sh + 1, (IW + 2 * pw - FW) // sw + 1
+    assert Y.shape == (N, OH, OW, OC)
+    for oh in range(OH):
+        for ow in range(OW):
+            th = min(IH - (oh * sh - ph), FH) - max(ph - oh * sh, 0)
+            tw = min(IW - (ow * sw - pw), FW) - max(pw - ow * sw, 0)
+            assert np.all(Y[0, oh, ow] == IC * th * tw)
+    c = oracle.mac_counts(N, IC, IH, IW, OC, FH, FW, (sh, sw), (ph, pw))
+    assert c["useful"] == int(Y.sum())   # N*IC*OC*S_h*S_w
+    assert c["dense"] == N * IC * OC * OH * OW * FH * FW
+    assert c["nominal_dilated"] == N * IC * OC * FH * FW * ((OH - 1) * sh + 1) * ((OW - 1) * sw + 1)
+
+
+def test_asymmetric_appendix_algorithms_reach_the_textbook_result(oracle):
+    from oracle import algorithms as alg
+
+    for i, g in enumerate(ASYM[::5]):
+        _, _, IH, IW, _, FH, FW, st, pd = g
+        g = (1, 2, IH, IW, 2, FH, FW, st, pd)
+        X, W, dY = make_asym(g, 9000 + i)
+        useful = oracle.mac_counts(*g)["useful"]
+        Y, m = alg.conv_v2(X, W, st, pd)
+        assert np.array_equal(Y, oracle.conv_fwd(X, W, st, pd)) and m == useful, g
+        C = oracle.kernel_split(W, st)
+        assert C.shape == (st[0], st[1], 2, -(-FH // st[0]), -(-FW // st[1]), 2)
+        dX, m, writes = alg.ks_deconv(dY, C, IH, IW, FH, FW, st, pd, trim=True)
+        assert np.all(writes == 1), g
+        assert np.array_equal(dX, oracle.deconv(dY, W, IH, IW, st, pd)) and m == useful, g
+        dW, m = alg.sk_dilated(X, dY, FH, FW, st, pd, trim=True)
+        assert np.array_equal(dW, oracle.wgrad(X, dY, FH, FW, st, pd)) and m == useful, g
+
+
+def test_asymmetric_kernel_split_partitions_the_filter(oracle):
+    rng = np.random.default_rng(13)
+    for FH, FW, sh, sw in [(3, 3, 2, 1), (4, 5, 2, 3), (7, 7, 3, 2), (2, 5, 4, 1), (1, 3, 2, 2)]:
+        OC, IC = 2, 3
+        W = (rng.permutation(OC * FH * FW * IC) + 1).astype(np.float32).reshape(OC, FH, FW, IC)
+        C = oracle.kernel_split(W, (sh, sw))
+        assert sorted(C[C != 0].tolist()) == sorted(W.ravel().tolist())
+        Wr = W[:, ::-1, ::-1, :]
+        for y in range(sh):
+            for x in range(sw):
+                rows = sorted(FH - 1 - fh for fh in range(FH) if fh % sh == y)
+                cols = sorted(FW - 1 - fw for fw in range(FW) if fw % sw == x)
+                if rows and cols:
+                    assert np.array_equal(C[y, x, :, :len(rows), :len(cols), :], Wr[:, rows][:, :, cols]), (FH, FW, sh, sw, y, x)
+
+
 def test_filter_transpose(oracle):
     rng = np.random.default_rng(2)
     W = rng.standard_normal((5, 3, 2, 7)).astype(np.float32)
