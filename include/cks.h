@@ -20,7 +20,7 @@
  * larger, input side -- also for cks_deconv2d, whose output size cannot be
  * recovered from OH when (H + 2*padding - FH) is not a multiple of stride),
  * OC output channels, FH x FW filter size, stride and padding applied to both
- * axes.
+ * axes (the *_hw entry points further down take them per axis).
  *
  * Ownership: the caller owns every buffer, workspaces included; the library
  * never allocates or frees device memory and keeps no device state.  Inputs are
@@ -105,6 +105,41 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
 int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
                              int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
                              void *ws, size_t ws_bytes, void *stream);
+
+/* ---- stride and padding given per axis ----
+ *
+ * Table I writes the strides as <sh sw> and the padding as <ph pw>, and
+ * Algorithms 1-3B are printed with both.  The *_hw entry points take them in
+ * that order: sh, ph act on the H axis (rows), sw, pw on the W axis (columns);
+ * OH = floor((H + 2*ph - FH) / sh) + 1, OW = floor((W + 2*pw - FW) / sw) + 1.
+ * Everything else -- tensors, layouts, ownership, execution, errors, the role
+ * of the workspace -- is as for the entry point of the same name without the
+ * suffix, which is the special case sh = sw = stride, ph = pw = padding (and
+ * calls it).  CKS_ERR_SHAPE if sh or sw < 1, ph or pw < 0, or the padded input
+ * is smaller than the filter on either axis.  KS-deconv then splits the
+ * filter into sh*sw sub-kernels; sub-kernel (y,x), y < sh, x < sw, has
+ * ceil((FH-y)/sh) x ceil((FW-x)/sw) taps (Section IV.B with the two strides
+ * kept apart), and Sk-dilated leaps sh rows and sw columns (Section IV.C).
+ * Geometries whose two axes differ always run the general kernels. */
+int cks_out_dims_hw(int H, int W, int FH, int FW, int sh, int sw, int ph, int pw, int *OH, int *OW);
+int64_t cks_useful_macs_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw);
+size_t cks_conv2d_fwd_workspace_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw);
+size_t cks_deconv2d_workspace_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw);
+size_t cks_dilated_conv2d_wgrad_workspace_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw);
+/* ConvV2, Algorithm 1: X [N,H,W,C] in, Wt [OC,FH,FW,C] in, Y [N,OH,OW,OC] out. */
+int cks_conv2d_fwd_hw(const float *X, const float *Wt, float *Y,
+                      int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                      void *ws, size_t ws_bytes, void *stream);
+/* KS-deconv-V2, Algorithms 2 / 2B: dY [N,OH,OW,OC] in, Wt [OC,FH,FW,C] in, dX [N,H,W,C] out;
+ * ws must hold cks_deconv2d_workspace_hw bytes. */
+int cks_deconv2d_hw(const float *dY, const float *Wt, float *dX,
+                    int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                    void *ws, size_t ws_bytes, void *stream);
+/* Sk-dilated-V2, Algorithm 3B: X [N,H,W,C] in, dY [N,OH,OW,OC] in, dW [OC,FH,FW,C] out;
+ * ws must hold cks_dilated_conv2d_wgrad_workspace_hw bytes. */
+int cks_dilated_conv2d_wgrad_hw(const float *X, const float *dY, float *dW,
+                                int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /* ---- the stages on their own (what the three calls above are made of) ---- */
 

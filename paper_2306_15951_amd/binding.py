@@ -17,7 +17,17 @@ _lib = None
 CKS_OK, CKS_ERR_NULL, CKS_ERR_SHAPE, CKS_ERR_WORKSPACE, CKS_ERR_HIP, CKS_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 _GEO = [ctypes.c_int] * 9
+_GEO_HW = [ctypes.c_int] * 11   # N, C, H, W, OC, FH, FW, sh, sw, ph, pw
+_OP_TAIL = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _PROTOTYPES = {
+    "cks_out_dims_hw": ([ctypes.c_int] * 8 + [ctypes.POINTER(ctypes.c_int)] * 2, ctypes.c_int),
+    "cks_useful_macs_hw": (_GEO_HW, ctypes.c_int64),
+    "cks_conv2d_fwd_workspace_hw": (_GEO_HW, ctypes.c_size_t),
+    "cks_deconv2d_workspace_hw": (_GEO_HW, ctypes.c_size_t),
+    "cks_dilated_conv2d_wgrad_workspace_hw": (_GEO_HW, ctypes.c_size_t),
+    "cks_conv2d_fwd_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + _OP_TAIL, ctypes.c_int),
+    "cks_deconv2d_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + _OP_TAIL, ctypes.c_int),
+    "cks_dilated_conv2d_wgrad_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + _OP_TAIL, ctypes.c_int),
     "cks_out_dims": ([ctypes.c_int] * 6 + [ctypes.POINTER(ctypes.c_int)] * 2, ctypes.c_int),
     "cks_useful_macs": (_GEO, ctypes.c_int64),
     "cks_conv2d_fwd_workspace": (_GEO, ctypes.c_size_t),
@@ -204,4 +214,60 @@ def cks_dilated_conv2d_wgrad_partials(X, dY, part, FH, FW, stride, padding):
 def cks_reduce_partials(part, dW):
     _check(lib().cks_reduce_partials(_ptr(part, "part"), _ptr(dW, "dW", tuple(part.shape[1:])),
                                      dW.numel(), part.shape[0], _stream()), "cks_reduce_partials")
+    return dW
+
+
+# ---- stride and padding per axis: stride = (sh, sw), padding = (ph, pw)
+
+def cks_out_dims_hw(H, W, FH, FW, stride, padding):
+    (sh, sw), (ph, pw) = stride, padding
+    oh, ow = ctypes.c_int(), ctypes.c_int()
+    _check(lib().cks_out_dims_hw(H, W, FH, FW, sh, sw, ph, pw, ctypes.byref(oh), ctypes.byref(ow)), "cks_out_dims_hw")
+    return oh.value, ow.value
+
+
+def cks_useful_macs_hw(N, C, H, W, OC, FH, FW, stride, padding):
+    return lib().cks_useful_macs_hw(N, C, H, W, OC, FH, FW, *stride, *padding)
+
+
+def cks_conv2d_fwd_workspace_hw(N, C, H, W, OC, FH, FW, stride, padding):
+    return lib().cks_conv2d_fwd_workspace_hw(N, C, H, W, OC, FH, FW, *stride, *padding)
+
+
+def cks_deconv2d_workspace_hw(N, C, H, W, OC, FH, FW, stride, padding):
+    return lib().cks_deconv2d_workspace_hw(N, C, H, W, OC, FH, FW, *stride, *padding)
+
+
+def cks_dilated_conv2d_wgrad_workspace_hw(N, C, H, W, OC, FH, FW, stride, padding):
+    return lib().cks_dilated_conv2d_wgrad_workspace_hw(N, C, H, W, OC, FH, FW, *stride, *padding)
+
+
+def cks_conv2d_fwd_hw(X, Wt, Y, stride, padding, ws=None):
+    N, H, W, C = X.shape
+    OC, FH, FW, _ = Wt.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    wp, wb = _ws(ws)
+    _check(lib().cks_conv2d_fwd_hw(_ptr(X, "X"), _ptr(Wt, "Wt", (OC, FH, FW, C)), _ptr(Y, "Y", (N, OH, OW, OC)),
+                                   N, C, H, W, OC, FH, FW, *stride, *padding, wp, wb, _stream()), "cks_conv2d_fwd_hw")
+    return Y
+
+
+def cks_deconv2d_hw(dY, Wt, dX, stride, padding, ws):
+    N, H, W, C = dX.shape
+    OC, FH, FW, _ = Wt.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    wp, wb = _ws(ws)
+    _check(lib().cks_deconv2d_hw(_ptr(dY, "dY", (N, OH, OW, OC)), _ptr(Wt, "Wt", (OC, FH, FW, C)), _ptr(dX, "dX"),
+                                 N, C, H, W, OC, FH, FW, *stride, *padding, wp, wb, _stream()), "cks_deconv2d_hw")
+    return dX
+
+
+def cks_dilated_conv2d_wgrad_hw(X, dY, dW, stride, padding, ws):
+    N, H, W, C = X.shape
+    OC, FH, FW, _ = dW.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    wp, wb = _ws(ws)
+    _check(lib().cks_dilated_conv2d_wgrad_hw(_ptr(X, "X"), _ptr(dY, "dY", (N, OH, OW, OC)), _ptr(dW, "dW", (OC, FH, FW, C)),
+                                             N, C, H, W, OC, FH, FW, *stride, *padding, wp, wb, _stream()),
+           "cks_dilated_conv2d_wgrad_hw")
     return dW

@@ -28,17 +28,21 @@ constexpr int kCUs = 256;  // compute units of one MI355X
 thread_local int g_last_hip_error = 0;
 
 struct Geo {
-    int N, C, H, W, OC, FH, FW, s, p, OH, OW;
+    int N, C, H, W, OC, FH, FW;
+    int sh, sw, ph, pw;   // stride and padding per axis (Table I: <sh sw>, <ph pw>)
+    int OH, OW;
+    bool same_on_both_axes() const { return sh == sw && ph == pw; }
 };
 
 inline bool fits_i31(long long v) { return v > 0 && v < (1LL << 31); }
 
-int check_geo(Geo &g, int N, int C, int H, int W, int OC, int FH, int FW, int s, int p)
+int check_geo(Geo &g, int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
 {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || s < 1 || p < 0) return CKS_ERR_SHAPE;
-    if ((long long)H + 2LL * p < FH || (long long)W + 2LL * p < FW) return CKS_ERR_SHAPE;
-    if (p > (1 << 20) || s > (1 << 20)) return CKS_ERR_SHAPE;
-    g = Geo{N, C, H, W, OC, FH, FW, s, p, (H + 2 * p - FH) / s + 1, (W + 2 * p - FW) / s + 1};
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || OC <= 0 || FH <= 0 || FW <= 0) return CKS_ERR_SHAPE;
+    if (sh < 1 || sw < 1 || ph < 0 || pw < 0) return CKS_ERR_SHAPE;
+    if ((long long)H + 2LL * ph < FH || (long long)W + 2LL * pw < FW) return CKS_ERR_SHAPE;
+    if (ph > (1 << 20) || pw > (1 << 20) || sh > (1 << 20) || sw > (1 << 20)) return CKS_ERR_SHAPE;
+    g = Geo{N, C, H, W, OC, FH, FW, sh, sw, ph, pw, (H + 2 * ph - FH) / sh + 1, (W + 2 * pw - FW) / sw + 1};
     if (!fits_i31((long long)N * H * W * C) || !fits_i31((long long)OC * FH * FW * C) ||
         !fits_i31((long long)N * g.OH * g.OW * OC))
         return CKS_ERR_SHAPE;
@@ -105,8 +109,10 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     P.dNT = make_fastdiv(P.nTiles);
     P.dMT = make_fastdiv(P.mTiles);
     P.dItemsW = make_fastdiv(P.itemsW);
-    P.dS = make_fastdiv(P.s);
-    P.pmods = P.p % P.s;
+    P.dSh = make_fastdiv(P.sh);
+    P.dSw = make_fastdiv(P.sw);
+    P.pmodsH = P.ph % P.sh;
+    P.pmodsW = P.pw % P.sw;
     {
         // output rows of a tile are one image apart
         const long long rowO = OP == OP_FWD ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;
@@ -167,37 +173,37 @@ RowRunParams rowrun_params(const Geo &g, const float *A, const float *B, float *
     RowRunParams P{};
     P.A = A; P.B = B; P.Out = Out;
     P.N = g.N; P.IC = g.C; P.IH = g.H; P.IW = g.W; P.OC = g.OC; P.OH = g.OH; P.OW = g.OW;
-    P.FH = g.FH; P.FW = g.FW; P.s = g.s; P.p = g.p;
-    P.CHp = (g.FH + g.s - 1) / g.s;
-    P.CWp = (g.FW + g.s - 1) / g.s;
+    P.FH = g.FH; P.FW = g.FW; P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw;
+    P.CHp = (g.FH + g.sh - 1) / g.sh;
+    P.CWp = (g.FW + g.sw - 1) / g.sw;
     if (OP == OP_FWD) {
         P.itemsH = g.OH; P.itemsW = g.OW;
-        P.rotH = ((g.p + g.s - 1) / g.s) % g.OH;          // output rows whose window starts in the padding
-        P.rotW = ((g.p + g.s - 1) / g.s) % g.OW;
+        P.rotH = ((g.ph + g.sh - 1) / g.sh) % g.OH;       // output rows whose window starts in the padding
+        P.rotW = ((g.pw + g.sw - 1) / g.sw) % g.OW;
     } else {
         P.itemsH = g.H; P.itemsW = g.W;
-        const int th = g.FH - 1 - g.p > 0 ? g.FH - 1 - g.p : 0, tw = g.FW - 1 - g.p > 0 ? g.FW - 1 - g.p : 0;
-        P.rotH = ((th + g.s - 1) / g.s) % g.H;            // positions per class whose dY window starts above row 0
-        P.rotW = ((tw + g.s - 1) / g.s) % g.W;
+        const int th = g.FH - 1 - g.ph > 0 ? g.FH - 1 - g.ph : 0, tw = g.FW - 1 - g.pw > 0 ? g.FW - 1 - g.pw : 0;
+        P.rotH = ((th + g.sh - 1) / g.sh) % g.H;          // positions per class whose dY window starts above row 0
+        P.rotW = ((tw + g.sw - 1) / g.sw) % g.W;
     }
     return P;
 }
 
-size_t split_bytes(int C, int OC, int FH, int FW, int s)
+size_t split_bytes(int C, int OC, int FH, int FW, int sh, int sw)
 {
-    return sizeof(float) * (size_t)s * s * C * ((FH + s - 1) / s) * ((FW + s - 1) / s) * OC;
+    return sizeof(float) * (size_t)sh * sw * C * ((FH + sh - 1) / sh) * ((FW + sw - 1) / sw) * OC;
 }
 
 template <int MODE>
-int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int s, hipStream_t st)
+int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int sh, int sw, hipStream_t st)
 {
     PackParams P{};
-    P.W = Wt; P.Out = Out; P.IC = C; P.OC = OC; P.FH = FH; P.FW = FW; P.s = s;
-    P.CHp = (FH + s - 1) / s;
-    P.CWp = (FW + s - 1) / s;
+    P.W = Wt; P.Out = Out; P.IC = C; P.OC = OC; P.FH = FH; P.FW = FW; P.sh = sh; P.sw = sw;
+    P.CHp = (FH + sh - 1) / sh;
+    P.CWp = (FW + sw - 1) / sw;
     P.ocTiles = (OC + 31) / 32;
     P.icTiles = (C + 31) / 32;
-    const long long slots = MODE == PACK_SPLIT ? (long long)s * s * P.CHp * P.CWp : (long long)FH * FW;
+    const long long slots = MODE == PACK_SPLIT ? (long long)sh * sw * P.CHp * P.CWp : (long long)FH * FW;
     const long long blocks = slots * P.ocTiles * P.icTiles;
     if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
     return launch(pack_filter<MODE>, P, (int)blocks, 0, st);
@@ -209,9 +215,11 @@ constexpr int kStripWgradGroups = kCUs;   // strip_wgrad: one workgroup (= one s
 
 // Few-channel geometries the strip kernels are instantiated for: 1 = 7x7 / stride 2 / 3 channels (ImageNet
 // stems), 2 = 3x3 / stride 1 / 3 channels, 3 = 3x3 / stride 2 / 3 channels (small-image stems); 0 = none.
-inline int strip_geometry(int FH, int FW, int C, int s)
+// All with the same stride and padding on both axes.
+inline int strip_geometry(const Geo &g)
 {
-    if (C != 3 || FH != FW) return 0;
+    const int FH = g.FH, FW = g.FW, C = g.C, s = g.sh;
+    if (!g.same_on_both_axes() || C != 3 || FH != FW) return 0;
     if (FH == 7 && s == 2) return 1;
     if (FH == 3 && s == 1) return 2;
     if (FH == 3 && s == 2) return 3;
@@ -224,7 +232,7 @@ int launch_strip_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hi
     using SG = StripGeo<FH, FW, IC, S>;
     StripFwdParams Q{};
     Q.X = X; Q.W = Wt; Q.Y = Y;
-    Q.N = g.N; Q.IH = g.H; Q.IW = g.W; Q.OC = g.OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = g.p;
+    Q.N = g.N; Q.IH = g.H; Q.IW = g.W; Q.OC = g.OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = g.ph;
     Q.nBands = (g.OW + 15) / 16;
     Q.nRowTiles = (g.OH + 3) / 4;
     Q.nT = (g.OC + 63) / 64;
@@ -244,7 +252,7 @@ int launch_strip_wgrad(const Geo &g, int GZ, const float *X, const float *dY, fl
 {
     StripWgradParams Q{};
     Q.X = X; Q.dY = dY; Q.part = part;
-    Q.N = g.N; Q.IH = g.H; Q.IW = g.W; Q.OC = g.OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = g.p;
+    Q.N = g.N; Q.IH = g.H; Q.IW = g.W; Q.OC = g.OC; Q.OH = g.OH; Q.OW = g.OW; Q.p = g.ph;
     Q.nBands = (g.OW + 15) / 16;
     Q.nRowTiles = (g.OH + 3) / 4;
     Q.tiles = g.N * Q.nBands * Q.nRowTiles;
@@ -282,7 +290,7 @@ WgradPlan plan_wgrad(const Geo &g)
     // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
     const long long J = (long long)g.FH * g.FW * g.C;
     // image stems: input strip in LDS (strip_wgrad), one segment per workgroup
-    if (strip_geometry(g.FH, g.FW, g.C, g.s) && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
+    if (strip_geometry(g) && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
         !tune && !getenv("CKS_TUNE_NO_STRIP_WGRAD")) {
         const long long tiles = (long long)g.N * ((g.OW + 15) / 16) * ((g.OH + 3) / 4);
         if (fits_i31(tiles)) {
@@ -366,13 +374,17 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
     P.dMT = make_fastdiv(P.mTiles);
     P.dTaps = make_fastdiv(P.FH * P.FW);
     P.dFW = make_fastdiv(P.FW);
-    P.dS = make_fastdiv(P.s);
+    P.dSh = make_fastdiv(P.sh);
+    P.dSw = make_fastdiv(P.sw);
     P.dGZ = make_fastdiv(P.GZ);
     P.dNC = make_fastdiv(P.N / KC > 0 ? P.N / KC : 1);
     P.bufStore = P.sliceElems * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_BUFFER_STORES");
     // batch-inner ordering with scalar chunk offsets (see pixel_gemm_fast)
+    // (its ceiling divisions shift their numerators by (FH + FW) strides: keep that within 31 bits)
+    const long long smax = P.sh > P.sw ? P.sh : P.sw;
     const bool fast = veca && vecb && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
-                      (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS");
+                      (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) &&
+                      (P.FH + P.FW + 2) * smax + P.IH + P.IW + P.FH + P.FW < (1LL << 30) && !getenv("CKS_TUNE_NO_FAST_LOADS");
     if (fast) return launch(pixel_gemm_fast<BM, BN, KC, WM, WN, WK>, P, blocks, lds, st);
     if (veca && vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
     if (veca) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
@@ -396,46 +408,19 @@ int launch_patch(PatchGemmParams P, bool veca, bool vecb, hipStream_t st)
     return launch(patch_gemm<WM, WN, WK, NBW, KC, false, false>, P, blocks, lds, st);
 }
 
-}  // namespace
 
-extern "C" {
-
-int cks_out_dims(int H, int W, int FH, int FW, int stride, int padding, int *OH, int *OW)
+int64_t useful_macs(const Geo &g)
 {
-    Geo g;
-    int rc = check_geo(g, 1, 1, H, W, 1, FH, FW, stride, padding);
-    if (rc != CKS_OK) return rc;
-    if (OH) *OH = g.OH;
-    if (OW) *OW = g.OW;
-    return CKS_OK;
-}
-
-int64_t cks_useful_macs(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
-{
-    Geo g;
-    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return -1;
-    auto S = [&](int I, int F, int O) {
+    auto S = [](int I, int F, int O, int s, int p) {
         int64_t t = 0;
         for (int o = 0; o < O; ++o) {
-            int i0 = o * g.s - g.p;
+            int i0 = o * s - p;
             int lo = -i0 > 0 ? -i0 : 0, hi = I - i0 < F ? I - i0 : F;
             if (hi > lo) t += hi - lo;
         }
         return t;
     };
-    return (int64_t)N * C * OC * S(H, FH, g.OH) * S(W, FW, g.OW);
-}
-
-size_t cks_conv2d_fwd_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
-{
-    (void)N; (void)C; (void)H; (void)W; (void)OC; (void)FH; (void)FW; (void)stride; (void)padding;
-    return 0;  // the forward operator reads the filter in its given layout
-}
-
-size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride)
-{
-    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || stride < 1) return 0;
-    return split_bytes(C, OC, FH, FW, stride);
+    return (int64_t)g.N * g.C * g.OC * S(g.H, g.FH, g.OH, g.sh, g.ph) * S(g.W, g.FW, g.OW, g.sw, g.pw);
 }
 
 // Few-channel KS-deconv (tap-stationary GEMM + LDS composing): geometry limits of scatter_deconv.
@@ -447,9 +432,11 @@ struct ScatterPlan {
     size_t headBytes, rowheadBytes;   // side buffers in the workspace, in this order
 };
 
-static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+ScatterPlan plan_scatter(const Geo &g)
 {
     ScatterPlan S{};
+    if (!g.same_on_both_axes()) return S;
+    const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW, stride = g.sh, padding = g.ph;
     const int J = FH * FW * C, sic = stride * C;
     if (C >= 8 || OC > 64 || OC % 4 != 0 || J > 160) return S;
     if ((long long)H * W * C * 4 >= (1LL << 31)) return S;   // an image is one raw buffer
@@ -505,57 +492,41 @@ static ScatterPlan plan_scatter(const Geo &g, int N, int C, int H, int W, int OC
     return S;
 }
 
-size_t cks_deconv2d_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+size_t deconv_workspace(const Geo &g)
 {
-    Geo g;
-    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
-    const size_t split = split_bytes(C, OC, FH, FW, stride);
-    const ScatterPlan S = plan_scatter(g, N, C, H, W, OC, FH, FW, stride, padding);
+    const size_t split = split_bytes(g.C, g.OC, g.FH, g.FW, g.sh, g.sw);
+    const ScatterPlan S = plan_scatter(g);
     return S.ok && S.headBytes + S.rowheadBytes > split ? S.headBytes + S.rowheadBytes : split;
 }
 
-int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+size_t wgrad_workspace(const Geo &g)
 {
-    Geo g;
-    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
-    return plan_wgrad(g).GZ;
-}
-
-size_t cks_dilated_conv2d_wgrad_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
-{
-    Geo g;
-    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, padding) != CKS_OK) return 0;
     const WgradPlan w = plan_wgrad(g);
-    return w.GZ > 1 ? sizeof(float) * (size_t)w.GZ * OC * FH * FW * C : 0;
+    return w.GZ > 1 ? sizeof(float) * (size_t)w.GZ * g.OC * g.FH * g.FW * g.C : 0;
 }
 
-int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
-                   int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
-                   void *ws, size_t ws_bytes, void *stream)
+int conv_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_t st)
 {
-    (void)ws; (void)ws_bytes;
-    Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
-    if (rc != CKS_OK) return rc;
     if (!X || !Wt || !Y) return CKS_ERR_NULL;
-    // Image stems (very few input channels): one GEMM over all pixels with the
-    // whole filter patch as contraction axis and the filter resident in LDS.
-    const int KP = (FH * FW * C + 15) / 16 * 16;
+    const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
     // image stems: input strip in LDS, addressing known at compile time
     if ((long long)H * W * C * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
-        switch (strip_geometry(FH, FW, C, stride)) {
-            case 1: return launch_strip_fwd<7, 7, 3, 2>(g, X, Wt, Y, (hipStream_t)stream);
-            case 2: return launch_strip_fwd<3, 3, 3, 1>(g, X, Wt, Y, (hipStream_t)stream);
-            case 3: return launch_strip_fwd<3, 3, 3, 2>(g, X, Wt, Y, (hipStream_t)stream);
+        switch (strip_geometry(g)) {
+            case 1: return launch_strip_fwd<7, 7, 3, 2>(g, X, Wt, Y, st);
+            case 2: return launch_strip_fwd<3, 3, 3, 1>(g, X, Wt, Y, st);
+            case 3: return launch_strip_fwd<3, 3, 3, 2>(g, X, Wt, Y, st);
             default: break;
         }
     }
+    // Other layers with very few input channels: one GEMM over all pixels with the
+    // whole filter patch as contraction axis and the filter resident in LDS.
+    const int KP = (FH * FW * C + 15) / 16 * 16;
     if (C < 8 && KP <= kPatchFwdMaxKP && (long long)N * H * W * C * 4 < (1LL << 31) &&
         (long long)N * g.OH * g.OW * OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_PATCH_FWD")) {
         PatchFwdParams Q{};
         Q.X = X; Q.W = Wt; Q.Y = Y;
         Q.N = N; Q.IC = C; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW;
-        Q.FH = FH; Q.FW = FW; Q.s = stride; Q.p = padding;
+        Q.FH = FH; Q.FW = FW; Q.sh = g.sh; Q.sw = g.sw; Q.ph = g.ph; Q.pw = g.pw;
         Q.KP = KP;
         Q.nT = (OC + 63) / 64;
         Q.mTiles = (int)(((long long)N * g.OH * g.OW + 63) / 64);
@@ -563,58 +534,42 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
         Q.tilesPerBlock = (Q.mTiles + groups - 1) / groups;
         const long long blocks = (long long)((Q.mTiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
         if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
-        return launch(patch_fwd, Q, (int)blocks, patch_fwd_lds_bytes(KP), (hipStream_t)stream, kPatchFwdThreads);
+        return launch(patch_fwd, Q, (int)blocks, patch_fwd_lds_bytes(KP), st, kPatchFwdThreads);
     }
     const bool vec = (C % 4 == 0) && aligned16(X) && aligned16(Wt);
-    return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), N, OC, vec, (hipStream_t)stream);
+    return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), N, OC, vec, st);
 }
 
-int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream)
+int kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int sh, int sw, hipStream_t st)
 {
-    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || stride < 1) return CKS_ERR_SHAPE;
-    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || sh < 1 || sw < 1 || sh > (1 << 20) || sw > (1 << 20)) return CKS_ERR_SHAPE;
+    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, sh, sw) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!Wt || !Cs) return CKS_ERR_NULL;
-    return launch_pack<PACK_SPLIT>(Wt, Cs, C, OC, FH, FW, stride, (hipStream_t)stream);
+    return launch_pack<PACK_SPLIT>(Wt, Cs, C, OC, FH, FW, sh, sw, st);
 }
 
-int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, int FW, void *stream)
+int deconv_presplit(const Geo &g, const float *dY, const float *Cs, float *dX, hipStream_t st)
 {
-    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0) return CKS_ERR_SHAPE;
-    if (!fits_i31((long long)C * OC * FH * FW)) return CKS_ERR_SHAPE;
-    if (!Wt || !Wout) return CKS_ERR_NULL;
-    return launch_pack<PACK_TRANSPOSE>(Wt, Wout, C, OC, FH, FW, 1, (hipStream_t)stream);
-}
-
-int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
-                          int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
-                          void *stream)
-{
-    Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
-    if (rc != CKS_OK) return rc;
-    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
+    if (!fits_i31((long long)(split_bytes(g.C, g.OC, g.FH, g.FW, g.sh, g.sw) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!dY || !Cs || !dX) return CKS_ERR_NULL;
-    const bool vec = (OC % 4 == 0) && aligned16(dY) && aligned16(Cs);
-    return dispatch_rowrun<OP_DECONV>(rowrun_params<OP_DECONV>(g, dY, Cs, dX), N, C, vec, (hipStream_t)stream);
+    const bool vec = (g.OC % 4 == 0) && aligned16(dY) && aligned16(Cs);
+    return dispatch_rowrun<OP_DECONV>(rowrun_params<OP_DECONV>(g, dY, Cs, dX), g.N, g.C, vec, st);
 }
 
-int cks_deconv2d(const float *dY, const float *Wt, float *dX,
-                 int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
-                 void *ws, size_t ws_bytes, void *stream)
+int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, size_t ws_bytes, hipStream_t st)
 {
-    Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
-    if (rc != CKS_OK) return rc;
-    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, stride) / sizeof(float)))) return CKS_ERR_SHAPE;
+    const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
+    if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, g.sh, g.sw) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!dY || !Wt || !dX) return CKS_ERR_NULL;
-    if (!ws || ws_bytes < cks_deconv2d_workspace(N, C, H, W, OC, FH, FW, stride, padding)) return CKS_ERR_WORKSPACE;
-    ScatterPlan S = plan_scatter(g, N, C, H, W, OC, FH, FW, stride, padding);
+    if (!ws || ws_bytes < deconv_workspace(g)) return CKS_ERR_WORKSPACE;
+    ScatterPlan S = plan_scatter(g);
     if (S.ok && aligned16(dY) && aligned16(ws) && !getenv("CKS_TUNE_NO_SCATTER")) {
-        hipStream_t st = (hipStream_t)stream;
+        const int stride = g.sh, padding = g.ph;   // the same on both axes (plan_scatter)
         S.P.dY = dY; S.P.W = Wt; S.P.dX = dX; S.P.head = (float *)ws;
         S.P.rowhead = (float *)((char *)ws + S.headBytes);
         const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
         const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2 && OC == 64;
+        int rc;
         if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, S.blocks, lds, st, kScatterThreads);
         else if (stem) rc = launch(scatter_deconv<10, true>, S.P, S.blocks, lds, st, kScatterStemThreads);
         else rc = launch(scatter_deconv<10, false>, S.P, S.blocks, lds, st, kScatterThreads);
@@ -642,26 +597,21 @@ int cks_deconv2d(const float *dY, const float *Wt, float *dX,
         return rc;
     }
     if (deconv_in_place_ok(g, dY, Wt))
-        return dispatch_rowrun<OP_DECONV_W>(rowrun_params<OP_DECONV_W>(g, dY, Wt, dX), N, C, true, (hipStream_t)stream);
-    rc = cks_kernel_split(Wt, (float *)ws, C, OC, FH, FW, stride, stream);
+        return dispatch_rowrun<OP_DECONV_W>(rowrun_params<OP_DECONV_W>(g, dY, Wt, dX), N, C, true, st);
+    int rc = kernel_split(Wt, (float *)ws, C, OC, FH, FW, g.sh, g.sw, st);
     if (rc != CKS_OK) return rc;
-    return cks_deconv2d_presplit(dY, (const float *)ws, dX, N, C, H, W, OC, FH, FW, stride, padding, stream);
+    return deconv_presplit(g, dY, (const float *)ws, dX, st);
 }
 
-int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *part,
-                                      int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
-                                      void *stream)
+int wgrad_partials(const Geo &g, const float *X, const float *dY, float *part, hipStream_t st)
 {
-    Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
-    if (rc != CKS_OK) return rc;
     if (!X || !dY || !part) return CKS_ERR_NULL;
+    const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
     const WgradPlan w = plan_wgrad(g);
     const bool veca = (OC % 4 == 0) && aligned16(dY);
     const bool vecb = (C % 4 == 0) && aligned16(X);
-    hipStream_t st = (hipStream_t)stream;
     if (w.patch == 4) {
-        switch (strip_geometry(FH, FW, C, stride)) {
+        switch (strip_geometry(g)) {
             case 1: return launch_strip_wgrad<7, 7, 3, 2>(g, w.GZ, X, dY, part, veca, st);
             case 2: return launch_strip_wgrad<3, 3, 3, 1>(g, w.GZ, X, dY, part, veca, st);
             case 3: return launch_strip_wgrad<3, 3, 3, 2>(g, w.GZ, X, dY, part, veca, st);
@@ -672,7 +622,7 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
         PatchGemmParams Q{};
         Q.X = X; Q.dY = dY; Q.Out = part;
         Q.N = N; Q.IC = C; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW;
-        Q.FH = FH; Q.FW = FW; Q.s = stride; Q.p = padding;
+        Q.FH = FH; Q.FW = FW; Q.sh = g.sh; Q.sw = g.sw; Q.ph = g.ph; Q.pw = g.pw;
         Q.GZ = w.GZ; Q.mTiles = w.mTiles;
         Q.total = w.GZ * w.mTiles;
         Q.perXcd = (Q.total + kXcds - 1) / kXcds;
@@ -689,7 +639,7 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
     PixelGemmParams P{};
     P.X = X; P.dY = dY; P.Out = part;
     P.N = N; P.IC = C; P.IH = H; P.IW = W; P.OC = OC; P.OH = g.OH; P.OW = g.OW;
-    P.FH = FH; P.FW = FW; P.s = stride; P.p = padding;
+    P.FH = FH; P.FW = FW; P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw;
     P.GZ = w.GZ; P.mTiles = w.mTiles; P.nTiles = w.nTiles;
     P.total = (int)total;
     P.perXcd = (P.total + kXcds - 1) / kXcds;
@@ -703,6 +653,189 @@ int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *pa
         case 5: return launch_pixel<128, 64, 16, 2, 2, 1>(P, veca, vecb, st);
         default: return launch_pixel<64, 128, 16, 2, 2, 1>(P, veca, vecb, st);
     }
+}
+
+int wgrad(const Geo &g, const float *X, const float *dY, float *dW, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!X || !dY || !dW) return CKS_ERR_NULL;
+    const int GZ = plan_wgrad(g).GZ;
+    const long slice = (long)g.OC * g.FH * g.FW * g.C;
+    if (GZ == 1)  // one segment: its "partial" result is the result
+        return wgrad_partials(g, X, dY, dW, (hipStream_t)stream);
+    if (!ws || ws_bytes < sizeof(float) * (size_t)GZ * slice) return CKS_ERR_WORKSPACE;
+    int rc = wgrad_partials(g, X, dY, (float *)ws, (hipStream_t)stream);
+    if (rc != CKS_OK) return rc;
+    return cks_reduce_partials((const float *)ws, dW, slice, GZ, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+// ---- stride and padding per axis
+
+int cks_out_dims_hw(int H, int W, int FH, int FW, int sh, int sw, int ph, int pw, int *OH, int *OW)
+{
+    Geo g;
+    int rc = check_geo(g, 1, 1, H, W, 1, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    if (OH) *OH = g.OH;
+    if (OW) *OW = g.OW;
+    return CKS_OK;
+}
+
+int64_t cks_useful_macs_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw) != CKS_OK) return -1;
+    return useful_macs(g);
+}
+
+size_t cks_conv2d_fwd_workspace_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
+{
+    (void)N; (void)C; (void)H; (void)W; (void)OC; (void)FH; (void)FW; (void)sh; (void)sw; (void)ph; (void)pw;
+    return 0;  // the forward operator reads the filter in its given layout
+}
+
+size_t cks_deconv2d_workspace_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw) != CKS_OK) return 0;
+    return deconv_workspace(g);
+}
+
+size_t cks_dilated_conv2d_wgrad_workspace_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw) != CKS_OK) return 0;
+    return wgrad_workspace(g);
+}
+
+int cks_conv2d_fwd_hw(const float *X, const float *Wt, float *Y,
+                      int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                      void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return conv_fwd(g, X, Wt, Y, (hipStream_t)stream);
+}
+
+int cks_deconv2d_hw(const float *dY, const float *Wt, float *dX,
+                    int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                    void *ws, size_t ws_bytes, void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return deconv(g, dY, Wt, dX, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int cks_dilated_conv2d_wgrad_hw(const float *X, const float *dY, float *dW,
+                                int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return wgrad(g, X, dY, dW, ws, ws_bytes, stream);
+}
+
+// ---- one stride and one padding for both axes
+
+int cks_out_dims(int H, int W, int FH, int FW, int stride, int padding, int *OH, int *OW)
+{
+    return cks_out_dims_hw(H, W, FH, FW, stride, stride, padding, padding, OH, OW);
+}
+
+int64_t cks_useful_macs(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    return cks_useful_macs_hw(N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+}
+
+size_t cks_conv2d_fwd_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    return cks_conv2d_fwd_workspace_hw(N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+}
+
+size_t cks_deconv2d_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    return cks_deconv2d_workspace_hw(N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+}
+
+size_t cks_dilated_conv2d_wgrad_workspace(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    return cks_dilated_conv2d_wgrad_workspace_hw(N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+}
+
+int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
+                   int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    return cks_conv2d_fwd_hw(X, Wt, Y, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, ws, ws_bytes, stream);
+}
+
+int cks_deconv2d(const float *dY, const float *Wt, float *dX,
+                 int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    return cks_deconv2d_hw(dY, Wt, dX, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, ws, ws_bytes, stream);
+}
+
+int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
+                             int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    return cks_dilated_conv2d_wgrad_hw(X, dY, dW, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, ws, ws_bytes, stream);
+}
+
+// ---- stages
+
+size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride)
+{
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || stride < 1) return 0;
+    return split_bytes(C, OC, FH, FW, stride, stride);
+}
+
+int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream)
+{
+    return kernel_split(Wt, Cs, C, OC, FH, FW, stride, stride, (hipStream_t)stream);
+}
+
+int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, int FW, void *stream)
+{
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0) return CKS_ERR_SHAPE;
+    if (!fits_i31((long long)C * OC * FH * FW)) return CKS_ERR_SHAPE;
+    if (!Wt || !Wout) return CKS_ERR_NULL;
+    return launch_pack<PACK_TRANSPOSE>(Wt, Wout, C, OC, FH, FW, 1, 1, (hipStream_t)stream);
+}
+
+int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
+                          int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                          void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+    if (rc != CKS_OK) return rc;
+    return deconv_presplit(g, dY, Cs, dX, (hipStream_t)stream);
+}
+
+int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    Geo g;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, stride, padding, padding) != CKS_OK) return 0;
+    return plan_wgrad(g).GZ;
+}
+
+int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *part,
+                                      int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                                      void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+    if (rc != CKS_OK) return rc;
+    return wgrad_partials(g, X, dY, part, (hipStream_t)stream);
 }
 
 int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream)
@@ -720,24 +853,6 @@ int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segment
     else hipLaunchKernelGGL((reduce_slices<1, 1>), grid, block, 0, st, part, dW, (long)elems, segments);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? CKS_OK : hip_fail(e);
-}
-
-int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
-                             int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
-                             void *ws, size_t ws_bytes, void *stream)
-{
-    Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, padding);
-    if (rc != CKS_OK) return rc;
-    if (!X || !dY || !dW) return CKS_ERR_NULL;
-    const int GZ = plan_wgrad(g).GZ;
-    const long slice = (long)OC * FH * FW * C;
-    if (GZ == 1)  // one segment: its "partial" result is the result
-        return cks_dilated_conv2d_wgrad_partials(X, dY, dW, N, C, H, W, OC, FH, FW, stride, padding, stream);
-    if (!ws || ws_bytes < sizeof(float) * (size_t)GZ * slice) return CKS_ERR_WORKSPACE;
-    rc = cks_dilated_conv2d_wgrad_partials(X, dY, (float *)ws, N, C, H, W, OC, FH, FW, stride, padding, stream);
-    if (rc != CKS_OK) return rc;
-    return cks_reduce_partials((const float *)ws, dW, slice, GZ, stream);
 }
 
 const char *cks_strerror(int status)

@@ -12,8 +12,8 @@ enum { PACK_SPLIT = 0, PACK_TRANSPOSE = 1 };
 
 struct PackParams {
     const float *W;   // [OC][FH][FW][IC]
-    float *Out;       // PACK_SPLIT: [s][s][IC][CHp][CWp][OC]   PACK_TRANSPOSE: [FH][FW][IC][OC]
-    int IC, OC, FH, FW, s, CHp, CWp;
+    float *Out;       // PACK_SPLIT: [sh][sw][IC][CHp][CWp][OC]   PACK_TRANSPOSE: [FH][FW][IC][OC]
+    int IC, OC, FH, FW, sh, sw, CHp, CWp;
     int ocTiles, icTiles;
 };
 
@@ -31,17 +31,17 @@ __global__ void __launch_bounds__(kThreads) pack_filter(const PackParams P)
     long out_ic;     // float distance between consecutive ic
     bool live = true;
     if (MODE == PACK_SPLIT) {
-        // slot = ((y*s + x)*CHp + ch)*CWp + cw.  Sub-kernel (y,x) has CH x CW
-        // taps; tap (ch,cw) is filter tap (y + (CH-1-ch)*s, x + (CW-1-cw)*s):
-        // the rotated filter sampled with step s.  Slots beyond (CH,CW) are
+        // slot = ((y*sw + x)*CHp + ch)*CWp + cw.  Sub-kernel (y,x) has CH x CW
+        // taps; tap (ch,cw) is filter tap (y + (CH-1-ch)*sh, x + (CW-1-cw)*sw):
+        // the rotated filter sampled with steps sh, sw.  Slots beyond (CH,CW) are
         // the zero padding of the 6-D tensor and are written as zeros.
         const int cw = slot % P.CWp, ch = (slot / P.CWp) % P.CHp;
         const int yx = slot / (P.CWp * P.CHp);
-        const int y = yx / P.s, x = yx - y * P.s;
-        const int CH = y < P.FH ? (P.FH - y + P.s - 1) / P.s : 0;
-        const int CW = x < P.FW ? (P.FW - x + P.s - 1) / P.s : 0;
-        fh = y + (CH - 1 - ch) * P.s;
-        fw = x + (CW - 1 - cw) * P.s;
+        const int y = yx / P.sw, x = yx - y * P.sw;
+        const int CH = y < P.FH ? (P.FH - y + P.sh - 1) / P.sh : 0;
+        const int CW = x < P.FW ? (P.FW - x + P.sw - 1) / P.sw : 0;
+        fh = y + (CH - 1 - ch) * P.sh;
+        fw = x + (CW - 1 - cw) * P.sw;
         live = ch < CH && cw < CW;
         out_ic = (long)P.CHp * P.CWp * P.OC;
         out_base = (long)yx * P.IC * out_ic + ((long)ch * P.CWp + cw) * P.OC;

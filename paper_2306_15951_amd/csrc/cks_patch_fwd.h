@@ -22,7 +22,8 @@ struct PatchFwdParams {
     const float *X;
     const float *W;
     float *Y;
-    int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
+    int N, IC, IH, IW, OC, OH, OW, FH, FW;
+    int sh, sw, ph, pw;   // stride and padding per axis
     int KP;             // J rounded up to a multiple of 16 (<= 192)
     int nT;             // 64-wide output-channel tiles
     int tilesPerBlock;  // pixel tiles each workgroup walks
@@ -97,11 +98,11 @@ __global__ void __launch_bounds__(kPatchFwdThreads) patch_fwd(const PatchFwdPara
             const int t2 = m0 / P.OW;
             int oh = t2 % P.OH;
             int n = t2 / P.OH;
-            const int ih0 = oh * P.s - P.p, iw0 = ow * P.s - P.p;
+            const int ih0 = oh * P.sh - P.ph, iw0 = ow * P.sw - P.pw;
             const bool fast = m0 + 16 <= M && ow + 16 <= P.OW && ih0 >= 0 && ih0 + P.FH <= P.IH && iw0 >= 0 &&
-                              iw0 + 15 * P.s + P.FW <= P.IW;
+                              iw0 + 15 * P.sw + P.FW <= P.IW;
             if (fast) {
-                const int s0 = ((n * P.IH + ih0) * P.IW + iw0) * P.IC * 4, ds = P.s * P.IC * 4;
+                const int s0 = ((n * P.IH + ih0) * P.IW + iw0) * P.IC * 4, ds = P.sw * P.IC * 4;
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
 #pragma unroll
@@ -116,7 +117,7 @@ __global__ void __launch_bounds__(kPatchFwdThreads) patch_fwd(const PatchFwdPara
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const bool live = m0 + i < M;
-                    const int h0 = oh * P.s - P.p, w0 = ow * P.s - P.p;
+                    const int h0 = oh * P.sh - P.ph, w0 = ow * P.sw - P.pw;
                     const int corner4 = (h0 * P.IW + w0) * P.IC * 4;   // may be negative
                     const int fh_lo = max(-h0, 0), j_lo = max(-w0, 0) * P.IC;
                     const unsigned fh_n = live ? (unsigned)max(min(P.IH - h0, P.FH) - fh_lo, 0) : 0u;

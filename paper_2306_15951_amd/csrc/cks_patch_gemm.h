@@ -29,7 +29,8 @@ struct PatchGemmParams {
     const float *X;
     const float *dY;
     float *Out;  // [GZ][OC][FH*FW*IC]
-    int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
+    int N, IC, IH, IW, OC, OH, OW, FH, FW;
+    int sh, sw, ph, pw;   // stride and padding per axis
     int GZ, mTiles, total, perXcd;
     long sliceElems;
 };
@@ -157,7 +158,7 @@ __global__ void __launch_bounds__(kThreads) patch_gemm(const PatchGemmParams P)
     float rbs[VECB ? 1 : NI];
     auto gload = [&]() {
         const bool live = kcur < kend;
-        const int ih0 = px.a * P.s - P.p, iw0 = px.b * P.s - P.p;     // top-left corner of the patch in X
+        const int ih0 = px.a * P.sh - P.ph, iw0 = px.b * P.sw - P.pw;     // top-left corner of the patch in X
         const float *ya = P.dY + (((long)px.n * P.OH + px.a) * P.OW + px.b) * P.OC + m0;
         const float *xb = P.X + (((long)px.n * P.IH + ih0) * P.IW + iw0) * P.IC;
         // filter rows / columns of this pixel's patch that lie inside X
@@ -329,7 +330,7 @@ __global__ void __launch_bounds__(kThreads) patch_gemm_fast(const PatchGemmParam
     auto gload = [&](bool live) {
         if (!live) return;   // uniform
         const int n1 = nch * KC;
-        const int ih0 = oh * P.s - P.p, iw0 = ow * P.s - P.p;     // top-left corner of the patches of this chunk
+        const int ih0 = oh * P.sh - P.ph, iw0 = ow * P.sw - P.pw;     // top-left corner of the patches of this chunk
         const int sa = (((n1 * P.OH + oh) * P.OW + ow) * P.OC) * 4;
 #pragma unroll
         for (int i = 0; i < NA; ++i)

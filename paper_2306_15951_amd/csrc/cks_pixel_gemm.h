@@ -3,10 +3,10 @@
 //
 // For one filter tap (fh,fw):
 //     dW[oc, fh, fw, ic] = sum over n, oh in [oh_s,oh_e), ow in [ow_s,ow_e)
-//                          dY[n, oh, ow, oc] * X[n, fh-p+oh*s, fw-p+ow*s, ic]
+//                          dY[n, oh, ow, oc] * X[n, fh-ph+oh*sh, fw-pw+ow*sw, ic]
 // i.e. a GEMM with rows oc, columns ic and the contraction index k running over
 // the pixels (n,oh,ow) of the tap's trimmed range.  dY is read exactly as it is
-// stored (no zero is ever inserted), X with a leaping step s.  One k is one
+// stored (no zero is ever inserted), X with a leaping step (sh, sw).  One k is one
 // contiguous OC-row of dY and one contiguous IC-row of X.
 //
 // The contraction axis is split at two levels:
@@ -25,11 +25,12 @@ struct PixelGemmParams {
     const float *X;
     const float *dY;
     float *Out;  // [GZ][OC][FH][FW][IC] partial sums (or dW itself when GZ == 1)
-    int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
+    int N, IC, IH, IW, OC, OH, OW, FH, FW;
+    int sh, sw, ph, pw;   // stride and padding per axis
     int GZ, mTiles, nTiles, total, perXcd;
     long sliceElems;  // OC*FH*FW*IC
     // divisors of the work decoding, prepared on the host (see FastDiv)
-    FastDiv dNT, dMT, dTaps, dFW, dS, dGZ, dNC;   // nTiles, mTiles, FH*FW, FW, s, GZ, N/KC (chunks per pixel of pixel_gemm_fast)
+    FastDiv dNT, dMT, dTaps, dFW, dSh, dSw, dGZ, dNC;   // nTiles, mTiles, FH*FW, FW, sh, sw, GZ, N/KC (chunks per pixel of pixel_gemm_fast)
     int bufStore;     // a slice is below 2 GiB: full tiles are stored through a buffer descriptor
 };
 
@@ -165,9 +166,9 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
     const int m0 = mt * BM, n0 = nt * BN;
 
     // Algorithm 3B: the (oh,ow) whose X element exists for this tap.
-    const int ih_s = fh - P.p, iw_s = fw - P.p;
-    const int oh_s = max(cdiv_any(-ih_s, P.s), 0), oh_e = min(P.OH, cdiv_any(P.IH - ih_s, P.s));
-    const int ow_s = max(cdiv_any(-iw_s, P.s), 0), ow_e = min(P.OW, cdiv_any(P.IW - iw_s, P.s));
+    const int ih_s = fh - P.ph, iw_s = fw - P.pw;
+    const int oh_s = max(cdiv_any(-ih_s, P.sh), 0), oh_e = min(P.OH, cdiv_any(P.IH - ih_s, P.sh));
+    const int ow_s = max(cdiv_any(-iw_s, P.sw), 0), ow_e = min(P.OW, cdiv_any(P.IW - iw_s, P.sw));
     const int nOH = max(oh_e - oh_s, 0), nOW = max(ow_e - ow_s, 0);
     const int Kt = P.N * nOH * nOW;
     const int seg = ((Kt + P.GZ - 1) / P.GZ + KC - 1) / KC * KC;
@@ -216,7 +217,7 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm(const PixelGemmParams P)
             const int oh = oh_s + px[r].a, ow = ow_s + px[r].b;
             const float *ya = P.dY + (((long)px[r].n * P.OH + oh) * P.OW + ow) * P.OC + m0 + lc;
             const float *xb =
-                P.X + (((long)px[r].n * P.IH + (oh * P.s + ih_s)) * P.IW + (ow * P.s + iw_s)) * P.IC + n0 + lc;
+                P.X + (((long)px[r].n * P.IH + (oh * P.sh + ih_s)) * P.IW + (ow * P.sw + iw_s)) * P.IC + n0 + lc;
 #pragma unroll
             for (int i = 0; i < PA; ++i) S.a[r][i] = load4<VECA>(ya + 64 * i, live ? P.OC - (m0 + lc + 64 * i) : 0);
 #pragma unroll
@@ -325,11 +326,11 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_fast(const PixelGemmParam
 
     // Algorithm 3B: the (oh,ow) whose X element exists for this tap.  ceil(a/s) for a of either sign
     // (a > -(FH + FW)): shift the numerator by a multiple of s that makes it non-negative.
-    const int ih_s = fh - P.p, iw_s = fw - P.p;
+    const int ih_s = fh - P.ph, iw_s = fw - P.pw;
     const int shiftK = P.FH + P.FW;
-    auto cdiv_s = [&](int a) { return fdiv(a + shiftK * P.s + P.s - 1, P.dS) - shiftK; };
-    const int oh_s = max(cdiv_s(-ih_s), 0), oh_e = min(P.OH, cdiv_s(P.IH - ih_s));
-    const int ow_s = max(cdiv_s(-iw_s), 0), ow_e = min(P.OW, cdiv_s(P.IW - iw_s));
+    auto cdiv_s = [&](int a, const FastDiv &d) { return fdiv(a + shiftK * d.d + d.d - 1, d) - shiftK; };
+    const int oh_s = max(cdiv_s(-ih_s, P.dSh), 0), oh_e = min(P.OH, cdiv_s(P.IH - ih_s, P.dSh));
+    const int ow_s = max(cdiv_s(-iw_s, P.dSw), 0), ow_e = min(P.OW, cdiv_s(P.IW - iw_s, P.dSw));
     const int nOH = max(oh_e - oh_s, 0), nOW = max(ow_e - ow_s, 0);
     const int NC = P.dNC.d;                        // chunks per (oh,ow): N / KC
     const int Ct = nOH * nOW * NC;                 // chunks of this tap
@@ -377,7 +378,7 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_fast(const PixelGemmParam
         if (!live) return;   // uniform
         const int oh = oh_s + pa_, ow = ow_s + pb_, n1 = nch * KC;
         const int sa = (((n1 * P.OH + oh) * P.OW + ow) * P.OC) * 4;
-        const int sb = (((n1 * P.IH + oh * P.s + ih_s) * P.IW + ow * P.s + iw_s) * P.IC) * 4;
+        const int sb = (((n1 * P.IH + oh * P.sh + ih_s) * P.IW + ow * P.sw + iw_s) * P.IC) * 4;
 #pragma unroll
         for (int r = 0; r < PK; ++r) {
 #pragma unroll

@@ -15,7 +15,7 @@
 //   ConvV2:    A = X,  B = W[oc][fh][fw][ic]              run over (fw, ic)
 //   KS-deconv: A = dY, B = Cs[y][x][ic][ch][cw][oc]       run over (cw, oc)
 //   KS-deconv without Stage 1: A = dY, B = W itself.  Sub-kernel (y,x)'s tap (ch,cw) is the filter tap
-//              (y + (CH-1-ch) s, x + (CW-1-cw) s); for it W[oc][fh][fw][ic] is a K x N matrix (oc x ic) with
+//              (y + (CH-1-ch) sh, x + (CW-1-cw) sw); for it W[oc][fh][fw][ic] is a K x N matrix (oc x ic) with
 //              N contiguous.  It is staged into LDS as it lies (K-major) and the B fragments are read one
 //              float per MFMA instead of four: Stage 1 then costs nothing at all.
 //
@@ -36,8 +36,9 @@ struct RowRunParams {
     const float *A;   // X (fwd) or dY (deconv)
     const float *B;   // W (fwd) or split kernels Cs (deconv)
     float *Out;       // Y (fwd) or dX (deconv)
-    int N, IC, IH, IW, OC, OH, OW, FH, FW, s, p;
-    int CHp, CWp;     // ceil(FH/s), ceil(FW/s): padded sub-kernel extents
+    int N, IC, IH, IW, OC, OH, OW, FH, FW;
+    int sh, sw, ph, pw;   // stride and padding per axis (Table I: <sh sw>, <ph pw>)
+    int CHp, CWp;     // ceil(FH/sh), ceil(FW/sw): padded sub-kernel extents
     // Work decomposition: one output position (of Y, resp. dX) times one tile.
     // Positions are issued roughly most expensive first: the list starts at
     // (rotH, rotW), the first position with an untrimmed window, and wraps
@@ -49,8 +50,8 @@ struct RowRunParams {
     int bandBlocks;       // workgroups per band = items per band * mTiles * nTiles
     int total;            // workgroups with work
     // divisors of the work decoding, prepared on the host (see FastDiv)
-    FastDiv dBand, dNT, dMT, dItemsW, dS;
-    int pmods;            // p mod s
+    FastDiv dBand, dNT, dMT, dItemsW, dSh, dSw;
+    int pmodsH, pmodsW;   // ph mod sh, pw mod sw
     int bufStore;         // the tile's BM output rows span less than 2 GiB: stores go through a buffer descriptor
 };
 
@@ -88,7 +89,7 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
     if (OP == OP_FWD) {
         // Algorithm 1: trim [fh_s,fh_e) x [fw_s,fw_e) of the filter at (oh,ow).
         const int oh = ph, ow = pw;
-        int ih_s = oh * P.s - P.p, iw_s = ow * P.s - P.p;
+        int ih_s = oh * P.sh - P.ph, iw_s = ow * P.sw - P.pw;
         int fh_s = max(-ih_s, 0), fh_e = min(P.IH - ih_s, P.FH);
         int fw_s = max(-iw_s, 0), fw_e = min(P.IW - iw_s, P.FW);
         R.nruns = max(fh_e - fh_s, 0);
@@ -106,10 +107,10 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         // Algorithm 2B: class (y,x) of (ih,iw), its sub-kernel extent CH x CW,
         // the window start (oh_s,ow_s) in dY and the trim [ch_s,ch_e) x [cw_s,cw_e).
         const int ih = ph, iw = pw;
-        const int qh = fdiv(ih + P.p, P.dS), qw = fdiv(iw + P.p, P.dS);
-        int y = ih + P.p - qh * P.s, x = iw + P.p - qw * P.s;
-        int CH = y < P.FH ? fdiv(P.FH - y + P.s - 1, P.dS) : 0;
-        int CW = x < P.FW ? fdiv(P.FW - x + P.s - 1, P.dS) : 0;
+        const int qh = fdiv(ih + P.ph, P.dSh), qw = fdiv(iw + P.pw, P.dSw);
+        int y = ih + P.ph - qh * P.sh, x = iw + P.pw - qw * P.sw;
+        int CH = y < P.FH ? fdiv(P.FH - y + P.sh - 1, P.dSh) : 0;
+        int CW = x < P.FW ? fdiv(P.FW - x + P.sw - 1, P.dSw) : 0;
         int oh_s = qh - (CH - 1), ow_s = qw - (CW - 1);
         int ch_s = max(-oh_s, 0), ch_e = min(P.OH - oh_s, CH);
         int cw_s = max(-ow_s, 0), cw_e = min(P.OW - ow_s, CW);
@@ -119,14 +120,14 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         R.aRun = (long)P.OW * P.OC;
         R.strideA = (long)P.OH * P.OW * P.OC;
         if (OP == OP_DECONV_W) {
-            // run r is sub-kernel row ch_s + r = filter row y + (CH-1-ch_s-r) s; likewise the columns
+            // run r is sub-kernel row ch_s + r = filter row y + (CH-1-ch_s-r) sh; likewise the columns
             R.strideB = (long)P.FH * P.FW * P.IC;
-            R.b0 = ((long)(y + (CH - 1 - ch_s) * P.s) * P.FW + (x + (CW - 1 - cw_s) * P.s)) * P.IC;
-            R.bRun = -(long)P.s * P.FW * P.IC;
-            R.bCw = -(long)P.s * P.IC;
+            R.b0 = ((long)(y + (CH - 1 - ch_s) * P.sh) * P.FW + (x + (CW - 1 - cw_s) * P.sw)) * P.IC;
+            R.bRun = -(long)P.sh * P.FW * P.IC;
+            R.bCw = -(long)P.sw * P.IC;
         } else {
             R.strideB = (long)P.CHp * P.CWp * P.OC;
-            R.b0 = (long)(y * P.s + x) * P.IC * R.strideB + ((long)ch_s * P.CWp + cw_s) * P.OC;
+            R.b0 = (long)(y * P.sw + x) * P.IC * R.strideB + ((long)ch_s * P.CWp + cw_s) * P.OC;
             R.bRun = (long)P.CWp * P.OC;
         }
         R.o0 = ((long)ih * P.IW + iw) * P.IC;   // Stage 3: the class result lands at its own (ih,iw)
@@ -192,8 +193,8 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     ph += P.rotH; if (ph >= P.itemsH) ph -= P.itemsH;   // rotH < itemsH
     pw += P.rotW; if (pw >= P.itemsW) pw -= P.itemsW;
     if (OP != OP_FWD) {
-        ph = class_major_index(ph, P.IH, P.dS, P.pmods);
-        pw = class_major_index(pw, P.IW, P.dS, P.pmods);
+        ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH);
+        pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW);
     }
     const int m0 = mt * BM, n0 = nt * BN;
 

@@ -13,6 +13,7 @@ from collections import namedtuple
 
 import numpy as np
 
+# stride / padding: an int (both axes) or a pair (vertical, horizontal)
 Layer = namedtuple("Layer", "name N IC IH IW OC FH FW stride padding")
 
 # Canonical conv-layer parameters of the benchmark configurations.  "cfg4a" is
@@ -32,9 +33,16 @@ LAYERS = {
 BASE_SEED = 230615951
 
 
+def pair(v):
+    """Stride or padding of a Layer as (vertical, horizontal); an int applies to both axes."""
+    if isinstance(v, (tuple, list)):
+        return int(v[0]), int(v[1])
+    return int(v), int(v)
+
+
 def out_hw(L):
-    return ((L.IH + 2 * L.padding - L.FH) // L.stride + 1,
-            (L.IW + 2 * L.padding - L.FW) // L.stride + 1)
+    (sh, sw), (ph, pw) = pair(L.stride), pair(L.padding)
+    return (L.IH + 2 * ph - L.FH) // sh + 1, (L.IW + 2 * pw - L.FW) // sw + 1
 
 
 def shapes(L):

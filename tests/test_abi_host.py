@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(cks):
     names = declared_symbols()
-    assert len(names) >= 14
+    assert len(names) >= 22
     L = ctypes.CDLL(cks.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
@@ -97,3 +97,27 @@ def test_useful_macs_agree_with_enumeration(cks, oracle):
         assert cks.cks_useful_macs(*g) == oracle.mac_counts(*g)["useful"], g
     assert 2 * cks.cks_useful_macs(1, 1, 4, 4, 1, 3, 3, 2, 1) == 50   # the paper's worked example
     assert cks.cks_useful_macs(1, 1, 2, 2, 1, 5, 5, 1, 1) == -1
+
+
+def test_per_axis_entry_points_on_the_host(cks, oracle):
+    """<sh sw>, <ph pw> of Table I: output size, validation and the useful multiply-add count."""
+    assert cks.cks_out_dims_hw(9, 12, 3, 5, (2, 3), (1, 2)) == (5, 4)
+    assert cks.cks_out_dims_hw(224, 224, 7, 7, (2, 2), (3, 3)) == cks.cks_out_dims(224, 224, 7, 7, 2, 3)
+    L = cks.lib()
+    assert L.cks_out_dims_hw(4, 4, 3, 3, 1, 0, 1, 1, None, None) == cks.CKS_ERR_SHAPE
+    assert L.cks_out_dims_hw(4, 4, 3, 3, 1, 1, 1, -1, None, None) == cks.CKS_ERR_SHAPE
+    assert L.cks_out_dims_hw(2, 8, 5, 3, 1, 1, 1, 4, None, None) == cks.CKS_ERR_SHAPE   # rows: 2 + 2 < 5
+    assert L.cks_out_dims_hw(8, 2, 3, 5, 1, 1, 4, 1, None, None) == cks.CKS_ERR_SHAPE   # columns
+    fake = ctypes.c_void_p(0x1000)
+    good = (2, 4, 8, 8, 4, 3, 3, 2, 1, 0, 1)
+    for fn in (L.cks_conv2d_fwd_hw, L.cks_deconv2d_hw, L.cks_dilated_conv2d_wgrad_hw):
+        assert fn(None, fake, fake, *good, None, 0, None) == cks.CKS_ERR_NULL
+        assert fn(fake, fake, fake, 2, 4, 8, 8, 4, 3, 3, 2, 0, 0, 1, None, 0, None) == cks.CKS_ERR_SHAPE
+    # the split tensor has sh*sw sub-kernels of ceil(FH/sh) x ceil(FW/sw) taps
+    assert L.cks_deconv2d_workspace_hw(*good) == 4 * 2 * 1 * 4 * 2 * 3 * 4
+    assert L.cks_deconv2d_hw(fake, fake, fake, *good, None, 0, None) == cks.CKS_ERR_WORKSPACE
+    for g in [(1, 1, 4, 4, 1, 3, 3, (2, 1), (1, 0)), (2, 3, 5, 8, 2, 4, 2, (3, 2), (3, 0)), (1, 2, 7, 5, 2, 1, 3, (2, 4), (0, 2)),
+              (1, 1, 7, 4, 1, 5, 2, (1, 3), (4, 1))]:
+        assert cks.cks_useful_macs_hw(*g) == oracle.mac_counts(*g)["useful"], g
+    g = (3, 2, 6, 9, 5, 3, 4, 2, 1)
+    assert cks.cks_useful_macs_hw(*g[:7], (2, 2), (1, 1)) == cks.cks_useful_macs(*g)

@@ -37,20 +37,25 @@ def nan_like(shape):
 
 def run_three(cks, L, X, W, dY):
     """All three operators of layer L through the ABI.  Outputs start as NaN so
-    an element the kernels forget to write cannot pass."""
+    an element the kernels forget to write cannot pass.  A layer whose stride or
+    padding is a pair goes through the per-axis entry points."""
     import torch
+    from paper_2306_15951_amd import synth
 
-    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
-    OH, OW = cks.cks_out_dims(L.IH, L.IW, L.FH, L.FW, L.stride, L.padding)
+    hw = isinstance(L.stride, tuple) or isinstance(L.padding, tuple)
+    st, pd = (synth.pair(L.stride), synth.pair(L.padding)) if hw else (L.stride, L.padding)
+    f = (lambda name: getattr(cks, name + "_hw")) if hw else (lambda name: getattr(cks, name))
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, st, pd)
+    OH, OW = f("cks_out_dims")(L.IH, L.IW, L.FH, L.FW, st, pd)
     Xd, Wd, dYd = dev(X), dev(W), dev(dY)
     Y = nan_like((L.N, OH, OW, L.OC))
     dX = nan_like((L.N, L.IH, L.IW, L.IC))
     dW = nan_like((L.OC, L.FH, L.FW, L.IC))
-    ws1 = torch.full((max(cks.cks_deconv2d_workspace(*g) // 4, 1),), float("nan"), device="cuda")
-    ws2 = torch.full((max(cks.cks_dilated_conv2d_wgrad_workspace(*g) // 4, 1),), float("nan"), device="cuda")
-    cks.cks_conv2d_fwd(Xd, Wd, Y, L.stride, L.padding)
-    cks.cks_deconv2d(dYd, Wd, dX, L.stride, L.padding, ws1)
-    cks.cks_dilated_conv2d_wgrad(Xd, dYd, dW, L.stride, L.padding, ws2)
+    ws1 = torch.full((max(f("cks_deconv2d_workspace")(*g) // 4, 1),), float("nan"), device="cuda")
+    ws2 = torch.full((max(f("cks_dilated_conv2d_wgrad_workspace")(*g) // 4, 1),), float("nan"), device="cuda")
+    f("cks_conv2d_fwd")(Xd, Wd, Y, st, pd)
+    f("cks_deconv2d")(dYd, Wd, dX, st, pd, ws1)
+    f("cks_dilated_conv2d_wgrad")(Xd, dYd, dW, st, pd, ws2)
     torch.cuda.synchronize()
     return Y.cpu().numpy(), dX.cpu().numpy(), dW.cpu().numpy()
 
@@ -204,6 +209,69 @@ def test_random_geometries(cks, oracle, geo):
 
     print("geometry", geo, flush=True)
     check_layer(cks, oracle, synth.Layer(*geo), seed=500 + int(geo[0][4:]), kinds=("int",))
+
+
+# Stride and padding that differ between the axes (Table I: <sh sw>, <ph pw>), through the *_hw entry
+# points: every general kernel and load path, and few-channel layers (which must not take the kernels
+# built for equal strides).
+ASYM = [
+    ("asym_fast_loads", 70, 32, 9, 12, 64, 3, 3, (1, 2), (1, 0)),
+    ("asym_in_place_s23", 64, 36, 13, 11, 96, 4, 5, (2, 3), (1, 2)),
+    ("asym_split_s31", 33, 20, 11, 9, 20, 3, 5, (3, 1), (0, 2)),
+    ("asym_scalar_loads", 17, 5, 9, 10, 7, 3, 2, (2, 1), (2, 0)),
+    ("asym_wide_pixel_fast", 32, 64, 8, 10, 72, 3, 3, (2, 1), (0, 1)),
+    ("asym_stride_gt_filter", 10, 8, 9, 9, 32, 1, 2, (2, 3), (0, 1)),
+    ("asym_pad_ge_filter", 12, 4, 5, 6, 8, 2, 3, (1, 2), (3, 1)),
+    ("asym_patch_ic16", 32, 16, 9, 10, 70, 3, 3, (1, 2), (0, 1)),
+    ("asym_patch_ic12_pixel_order", 9, 12, 11, 9, 40, 3, 3, (2, 1), (1, 1)),
+    ("asym_rgb_7x7_pad", 3, 3, 30, 41, 64, 7, 7, (2, 2), (3, 2)),
+    ("asym_rgb_3x3", 5, 3, 20, 70, 16, 3, 3, (1, 2), (1, 1)),
+    ("asym_gray", 4, 1, 12, 13, 70, 5, 3, (3, 2), (2, 0)),
+    ("asym_remainder_rows", 16, 12, 8, 9, 32, 3, 3, (2, 3), (0, 0)),
+    ("asym_one_by_one", 40, 48, 5, 6, 96, 1, 1, (2, 1), (0, 0)),
+    ("asym_tall_filter", 6, 8, 14, 5, 16, 7, 1, (3, 1), (3, 0)),
+]
+
+
+@pytest.mark.parametrize("geo", ASYM, ids=[g[0] for g in ASYM])
+def test_per_axis_stride_and_padding(cks, oracle, geo):
+    from paper_2306_15951_amd import synth
+
+    print("geometry", geo, flush=True)
+    check_layer(cks, oracle, synth.Layer(*geo), seed=700 + [g[0] for g in ASYM].index(geo[0]))
+
+
+def random_asymmetric_geometries(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        C = int(rng.choice([1, 3, 4, 5, 8, 16, 20, 32, 36, 64]))
+        OC = int(rng.choice([1, 4, 8, 20, 32, 64, 70, 96]))
+        FH, FW = (int(rng.choice([1, 2, 3, 3, 4, 5, 7])) for _ in range(2))
+        st = (int(rng.choice([1, 2, 3, 4])), int(rng.choice([1, 2, 3, 4])))
+        pd = (int(rng.integers(0, FH + 1)), int(rng.integers(0, FW + 1)))
+        if st[0] == st[1] and pd[0] == pd[1]:
+            continue
+        H, W = int(rng.integers(1, 33)), int(rng.integers(1, 33))
+        N = int(rng.choice([1, 2, 5, 16, 32, 33, 64, 70]))
+        if H + 2 * pd[0] < FH or W + 2 * pd[1] < FW:
+            continue
+        OH, OW = (H + 2 * pd[0] - FH) // st[0] + 1, (W + 2 * pd[1] - FW) // st[1] + 1
+        if N * OH * OW * OC * FH * FW * C > 3e8:
+            continue
+        out.append(("arand%02d" % len(out), N, C, H, W, OC, FH, FW, st, pd))
+    return out
+
+
+RANDOM_ASYM = random_asymmetric_geometries(32, 20230616)
+
+
+@pytest.mark.parametrize("geo", RANDOM_ASYM, ids=[g[0] for g in RANDOM_ASYM])
+def test_random_per_axis_geometries(cks, oracle, geo):
+    from paper_2306_15951_amd import synth
+
+    print("geometry", geo, flush=True)
+    check_layer(cks, oracle, synth.Layer(*geo), seed=900 + int(geo[0][5:]), kinds=("int",))
 
 
 def structured_samples(shape, rng, n_random):
