@@ -265,7 +265,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=200)   # the box needs some tens of milliseconds of load to reach its steady state
     ap.add_argument("--config", default="cfg1")
     ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (extra JSON field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -338,7 +338,7 @@ def main():
                 continue
             del B
             torch.cuda.empty_cache()
-            B, rr = bench_layer(synth.LAYERS[name], max(a.steps // 4, 10), max(a.warmup, 5))
+            B, rr = bench_layer(synth.LAYERS[name], max(a.steps // 2, 10), max(a.warmup, 100))
             others[name] = rr
         line["other_configs"] = others
     print(json.dumps(line))

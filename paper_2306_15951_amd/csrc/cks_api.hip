@@ -78,6 +78,13 @@ template <typename K, typename P>
 int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st, int threads = kThreads)
 {
     if (lds > 160 * 1024) return CKS_ERR_SHAPE;
+    if (const char *t = getenv("CKS_TUNE_WG_PER_CU")) {   // tuning experiments only: cap the workgroups resident per compute unit
+        const int n = atoi(t);
+        if (n > 0) {
+            const size_t want = (size_t)(160 * 1024 / n) / 256 * 256;
+            if (want > lds) lds = want;
+        }
+    }
     if (lds > 64 * 1024) {
         hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel));
         if (e != hipSuccess) return hip_fail(e);
@@ -290,8 +297,9 @@ WgradPlan plan_wgrad(const Geo &g)
     // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
     const long long J = (long long)g.FH * g.FW * g.C;
     // image stems: input strip in LDS (strip_wgrad), one segment per workgroup
+    // (an image of X and one of dY, plus a tile's rows below it, are each addressed with 31 bits of bytes)
     if (strip_geometry(g) && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
-        !tune && !getenv("CKS_TUNE_NO_STRIP_WGRAD")) {
+        ((long long)g.OH + 4) * g.OW * g.OC * 4 < (1LL << 31) && !tune && !getenv("CKS_TUNE_NO_STRIP_WGRAD")) {
         const long long tiles = (long long)g.N * ((g.OW + 15) / 16) * ((g.OH + 3) / 4);
         if (fits_i31(tiles)) {
             w.patch = 4;

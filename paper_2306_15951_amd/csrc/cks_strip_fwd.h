@@ -46,10 +46,14 @@ struct StripGeo {
     static constexpr int L = FW * IC, J = FH * L, STEPS = (J + 1) / 2;
     static constexpr int SR = (TH - 1) * S + FH;              // strip rows
     static constexpr int SWF = ((TW - 1) * S + FW) * IC;      // strip floats per row
-    static constexpr int RP = SWF + 1;                        // row pitch
-    static constexpr int STRIP = SR * RP + 1;                 // + one word that stays zero
+    static constexpr int PASSES = (SWF + 63) / 64;            // 64-lane passes that cover a row
+    // Row pitch: SWF + 1 modulo the 64 banks (neighbouring rows then start 48 or 55 banks apart, which keeps the
+    // MFMA lanes' reads conflict-free), and at least 64 * PASSES, so that the staging waves can write whole
+    // passes without masking lanes (the floats past SWF are never read).
+    static constexpr int RP = SWF + 1 + (64 * PASSES - (SWF + 1) + 63) / 64 * 64;
+    static constexpr int SRA = (SR + 3) / 4 * 4;              // rows allocated: every staging wave the same number
+    static constexpr int STRIP = SRA * RP + 1;                // + one word that stays zero
     static constexpr int LDW = (2 * STEPS) | 1;               // filter row pitch, odd: conflict-free column reads
-    static constexpr int PASSES = (SWF + 63) / 64;
     static constexpr size_t lds_bytes() { return (size_t)(64 * LDW + 2 * STRIP) * sizeof(float); }
 };
 
@@ -57,15 +61,18 @@ struct StripGeo {
 // floats l, l+64, ... of a row.  The image is one raw buffer, the row a scalar offset; floats that
 // lie outside the row (left/right padding) carry an offset beyond the buffer and read as zero,
 // rows outside the image are not read and staged as zeros.
+// A wave that shares its SIMD with an MFMA wave gets an issue slot only every few dozen cycles, whatever
+// the instruction, so this path is written for instruction count: a strip whose rows all lie inside the
+// image (most) is fetched without per-row tests, and the LDS writes are unconditional.
 template <class G>
 struct StripStager {
-    static constexpr int RROWS = (G::SR + 3) / 4;
+    static constexpr int RROWS = G::SRA / 4;
     static constexpr int kBeyond = (int)0x80000000u;
     float v[RROWS][G::PASSES];
     int voff[G::PASSES];
     int band = -1;
 
-    // tile = (image n, band c of 16 output columns, row tile t of 4 output rows)
+    // tile = (image n, band c of 16 output columns, row tile t of 4 output rows); all wave-uniform
     __device__ __forceinline__ void fetch(const float *X, int n, int c, int t, int pw, int lane, int IH, int IW, int p)
     {
         const int rowFloats = IW * G::IC_;
@@ -80,28 +87,37 @@ struct StripStager {
         }
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float *>(X) + (long)n * IH * rowFloats, 0, IH * rowFloats * 4, 0x00020000);
-        const int ih0 = 4 * t * G::S_ - p;
+        const int ih0 = 4 * t * G::S_ - p, rowB = rowFloats * 4;
+        if (ih0 >= 0 && ih0 + G::SR <= IH) {
+            int soff = (ih0 + pw) * rowB;
+#pragma unroll
+            for (int j = 0; j < RROWS; ++j, soff += 4 * rowB) {
+                if (4 * j + 3 < G::SR || pw + 4 * j < G::SR) {   // (the rows past SR exist in LDS only)
+#pragma unroll
+                    for (int q = 0; q < G::PASSES; ++q)
+                        v[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], soff, 0));
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < RROWS; ++j) {
             const int ih = ih0 + pw + 4 * j;
             const bool in = pw + 4 * j < G::SR && ih >= 0 && ih < IH;   // uniform
 #pragma unroll
             for (int q = 0; q < G::PASSES; ++q)
-                v[j][q] = in ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], ih * rowFloats * 4, 0)) : 0.f;
+                v[j][q] = in ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], ih * rowB, 0)) : 0.f;
         }
     }
-    // strip: start of the strip buffer to fill
+    // strip: start of the strip buffer to fill.  Whole passes and all RROWS rows are written: what lies
+    // past SWF or SR is never read.
     __device__ __forceinline__ void stage(float *strip, int pw, int lane) const
     {
         float *dst = strip + pw * G::RP + lane;
 #pragma unroll
-        for (int j = 0; j < RROWS; ++j) {
-            if (pw + 4 * j < G::SR) {
+        for (int j = 0; j < RROWS; ++j)
 #pragma unroll
-                for (int q = 0; q < G::PASSES; ++q)
-                    if (lane + 64 * q < G::SWF) dst[4 * j * G::RP + 64 * q] = v[j][q];
-            }
-        }
+            for (int q = 0; q < G::PASSES; ++q) dst[4 * j * G::RP + 64 * q] = v[j][q];
     }
 };
 
@@ -165,36 +181,43 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
         if (oc0 + r < P.OC) Ws[r * LDW + j] = P.W[(long)(oc0 + r) * J + j];
     }
 
-    // tile index -> (image, band, row tile); row tiles fastest, so a workgroup runs down a band
-    auto decode = [&](int tile, int &n, int &c, int &t) {
-        t = tile % P.nRowTiles;
-        const int q = tile / P.nRowTiles;
-        c = q % P.nBands;
-        n = q / P.nBands;
+    // tile index -> (image, band, row tile); row tiles fastest, so a workgroup runs down a band.  Decoded once;
+    // every wave then advances its own cursor (divisions by kernel arguments run on the vector ALU).
+    int cn, cc, ct;
+    {
+        ct = tile_beg % P.nRowTiles;
+        const int q = tile_beg / P.nRowTiles;
+        cc = q % P.nBands;
+        cn = q / P.nBands;
+    }
+    auto advance = [&]() {
+        if (++ct == P.nRowTiles) { ct = 0; if (++cc == P.nBands) { cc = 0; ++cn; } }
     };
 
     if (wave >= 4) {
         // ---------------------------------------------------------------- staging waves
         const int pw = wave - 4;
         StripStager<G> stager;
-        auto fetch = [&](int tile) {
-            if (tile >= tile_end) return;   // uniform
-            int n, c, t;
-            decode(tile, n, c, t);
-            stager.fetch(P.X, n, c, t, pw, lane, P.IH, P.IW, P.p);
+        int ftile = tile_beg;   // the tile fetched next: the cursor's
+        auto fetch = [&]() {
+            if (ftile >= tile_end) return;   // uniform
+            ++ftile;
+            stager.fetch(P.X, __builtin_amdgcn_readfirstlane(cn), __builtin_amdgcn_readfirstlane(cc),
+                         __builtin_amdgcn_readfirstlane(ct), pw, lane, P.IH, P.IW, P.p);
+            advance();
         };
         auto stage = [&](int tile, int buf) {
             if (tile < tile_end) stager.stage(Ss + buf * STRIP, pw, lane);
         };
-        fetch(tile_beg);
+        fetch();                 // tile_beg
         stage(tile_beg, 0);
-        fetch(tile_beg + 1);
+        fetch();                 // tile_beg + 1
         __syncthreads();
         // the loads of tile t+2 are issued as soon as the registers of tile t+1 have gone to LDS: they
         // have a whole tile's time to arrive
         for (int tile = tile_beg; tile < tile_end; ++tile) {
             stage(tile + 1, (tile + 1 - tile_beg) & 1);
-            fetch(tile + 2);
+            fetch();             // tile + 2
             __syncthreads();
         }
         return;
@@ -231,8 +254,9 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
         float av[G::STEPS], bv[G::STEPS];
         StripKLoop<G, 0>::run(av, bv, acc, a_same + sb, a_wrap + sb, a_last + sb, b_ptr);
 
-        int n, c, tt;
-        decode(tile, n, c, tt);
+        const int n = __builtin_amdgcn_readfirstlane(cn), c = __builtin_amdgcn_readfirstlane(cc),
+                  tt = __builtin_amdgcn_readfirstlane(ct);
+        advance();
         const int ow0 = c * 16, cols = min(16, P.OW - ow0);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {

@@ -82,31 +82,53 @@ __global__ void __launch_bounds__(kStripThreads) strip_wgrad(const StripWgradPar
         // ---------------------------------------------------------------- staging waves
         const int pw = wave - 4, ptid = tid - 256;
         StripStager<G> stager;
+        // (written for instruction count, see StripStager: a tile cursor advanced without divisions, one dY
+        // descriptor per image, 32-bit scalar row offsets, no per-row tests when the tile's rows all exist)
+        int fn, fc, ft, ftile = tile_beg;   // the tile fetched next
+        decode(tile_beg < P.tiles ? tile_beg : 0, fn, fc, ft);
         // dY: tile row th is min(16, OW-ow0)*OC contiguous floats; thread f takes floats 4f..4f+3 of it
         const bool a_lane = 4 * ptid < 16 * P.OC;
         const int a_px = a_lane ? (4 * ptid) / P.OC : 0, a_oc = a_lane ? 4 * ptid - a_px * P.OC : 0;
         float *a_dst = As + a_px * LDY + a_oc;   // VEC: OC % 4 == 0, the four floats are one pixel's
         float4 areg[4];
-        auto fetch = [&](int tile) {
-            if (tile >= tile_end) return;   // uniform
-            int n, c, t;
-            decode(tile, n, c, t);
+        constexpr int kBeyond = (int)0x80000000u;
+        const int imgY = P.OH * P.OW * P.OC;     // floats of dY per image (the host checks: below 2 GiB)
+        int a_band = -1, a_voff[VEC ? 1 : 4];    // byte offsets of this thread's floats in a tile row, or kBeyond
+        auto fetch = [&]() {
+            if (ftile >= tile_end) return;   // uniform
+            // (made scalar explicitly: the cursor is uniform, but lives across divergent code)
+            const int n = __builtin_amdgcn_readfirstlane(fn), c = __builtin_amdgcn_readfirstlane(fc), t = __builtin_amdgcn_readfirstlane(ft);
+            ++ftile;
+            if (++ft == P.nRowTiles) { ft = 0; if (++fc == P.nBands) { fc = 0; ++fn; } }
             stager.fetch(P.X, n, c, t, pw, lane, P.IH, P.IW, P.p);
             if (!a_lane) return;
-            const int ow0 = c * 16, a_bytes = min(16, P.OW - ow0) * P.OC * 4;
+            const int ow0 = c * 16;
+            if (c != a_band) {   // uniform: floats past the last output column of the band read as zero
+                a_band = c;
+                const int a_bytes = min(16, P.OW - ow0) * P.OC * 4;
 #pragma unroll
-            for (int th = 0; th < 4; ++th) {
-                const int oh = 4 * t + th;
-                const long off = (((long)n * P.OH + min(oh, P.OH - 1)) * P.OW + ow0) * P.OC;
-                const __amdgpu_buffer_rsrc_t rs =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + off), 0, oh < P.OH ? a_bytes : 0, 0x00020000);
+                for (int i = 0; i < (VEC ? 1 : 4); ++i) a_voff[i] = 16 * ptid + 4 * i < a_bytes ? 16 * ptid + 4 * i : kBeyond;
+            }
+            const __amdgpu_buffer_rsrc_t rs =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + (long)n * imgY), 0, imgY * 4, 0x00020000);
+            int soff = ((4 * t) * P.OW + ow0) * P.OC * 4;
+            const int rowB = P.OW * P.OC * 4;
+            if (VEC && 4 * t + 4 <= P.OH) {   // uniform
+#pragma unroll
+                for (int th = 0; th < 4; ++th, soff += rowB)
+                    areg[th] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff[0], soff, 0));
+                return;
+            }
+#pragma unroll
+            for (int th = 0; th < 4; ++th, soff += rowB) {
+                const bool in = 4 * t + th < P.OH;   // uniform; a row below the map reads as zero
                 if constexpr (VEC) {
-                    areg[th] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, 16 * ptid, 0, 0));
+                    areg[th] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rs, in ? a_voff[0] : kBeyond, soff, 0));
                 } else {
-                    areg[th].x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, 16 * ptid, 0, 0));
-                    areg[th].y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, 16 * ptid + 4, 0, 0));
-                    areg[th].z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, 16 * ptid + 8, 0, 0));
-                    areg[th].w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, 16 * ptid + 12, 0, 0));
+                    areg[th].x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, in ? a_voff[0] : kBeyond, soff, 0));
+                    areg[th].y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, in ? a_voff[VEC ? 0 : 1] : kBeyond, soff, 0));
+                    areg[th].z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, in ? a_voff[VEC ? 0 : 2] : kBeyond, soff, 0));
+                    areg[th].w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, in ? a_voff[VEC ? 0 : 3] : kBeyond, soff, 0));
                 }
             }
         };
@@ -130,15 +152,15 @@ __global__ void __launch_bounds__(kStripThreads) strip_wgrad(const StripWgradPar
                 }
             }
         };
-        fetch(tile_beg);
+        fetch();                 // tile_beg
         stage(tile_beg, 0);
-        fetch(tile_beg + 1);
+        fetch();                 // tile_beg + 1
         __syncthreads();
         // the loads of tile t+2 are issued as soon as the registers of tile t+1 have gone to LDS: they
         // have a whole tile's time to arrive
         for (int tile = tile_beg; tile < tile_end; ++tile) {
             stage(tile + 1, (tile + 1 - tile_beg) & 1);
-            fetch(tile + 2);
+            fetch();             // tile + 2
             __syncthreads();
         }
     } else {
