@@ -112,6 +112,64 @@ def measured_traffic(workload, kernel_prefix):
     return None
 
 
+def mfma_probe(fn=None, busy_ms=30.0):
+    """What the fp32 matrix cores sustain on this machine (libcks_probe.so, include/cks_probe.h), each case run
+    back to back for busy_ms after 20 ms of the same load, with the shader clock sampled from a second
+    stream meanwhile.  With fn (a callable that launches work on the current stream) only the clock under
+    that load is measured."""
+    import ctypes
+    import numpy as np
+    import torch
+
+    path = os.path.join(ROOT, "paper_2306_15951_amd", "libcks_probe.so")
+    if not os.path.exists(path):
+        raise ImportError("libcks_probe.so is not built: run __graft_entry__.build()")
+    P = ctypes.CDLL(path)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    P.cks_probe_mfma_registers.argtypes = [vp, ci, ci, ci, vp]
+    P.cks_probe_mfma_lds.argtypes = [vp, ci, ci, ci, ci, vp]
+    P.cks_probe_clock_samples.argtypes = [vp, ci, ci, vp]
+    out = torch.zeros(256, device="cuda:0")
+    side = torch.cuda.Stream()
+    n = 600                                     # samples about 27 us apart: 16 ms
+    stamps = torch.zeros(2 * n, dtype=torch.int64, device="cuda:0")
+    st = lambda: ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def run(launch):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); launch(); launch(); e1.record(); torch.cuda.synchronize()
+        per = max(e0.elapsed_time(e1) / 2, 1e-3)
+        for _ in range(int(20.0 / per) + 1):
+            launch()
+        reps = int(busy_ms / per) + 1
+        assert P.cks_probe_clock_samples(stamps.data_ptr(), n, 8, ctypes.c_void_p(side.cuda_stream)) == 0
+        e0.record()
+        for _ in range(reps):
+            launch()
+        e1.record()
+        torch.cuda.synchronize()
+        h = stamps.cpu().numpy().reshape(n, 2)
+        ghz = float(h[-1, 1] - h[0, 1]) / (float(h[-1, 0] - h[0, 0]) / 100e6) / 1e9
+        return e0.elapsed_time(e1) / reps, ghz
+
+    if fn is not None:
+        ms, ghz = run(fn)
+        return {"ms_per_call": ms, "shader_clock_ghz": ghz}
+    res = {}
+    iters, chunks, items = 4096, 18, 64
+    cases = (
+        ("registers_constant_operands", 1024.0 * 4 * iters * 8, lambda: P.cks_probe_mfma_registers(out.data_ptr(), 1024, iters, 0, st())),
+        ("registers_varying_operands", 1024.0 * 4 * iters * 8, lambda: P.cks_probe_mfma_registers(out.data_ptr(), 1024, iters, 1, st())),
+        ("lds_fed_k_loop_constant_operands", 1024.0 * 4 * items * chunks * 16, lambda: P.cks_probe_mfma_lds(out.data_ptr(), 1024, chunks, items, 0, st())),
+        ("lds_fed_k_loop_varying_operands", 1024.0 * 4 * items * chunks * 16, lambda: P.cks_probe_mfma_lds(out.data_ptr(), 1024, chunks, items, 1, st())),
+    )
+    for name, mfmas, launch in cases:
+        ms, ghz = run(launch)
+        tf = mfmas * 4096 / ms / 1e9
+        res[name] = {"tflops": tf, "pct_of_published_peak": 100 * tf / PEAK_FP32_MFMA_TFLOPS, "shader_clock_ghz": ghz}
+    return res
+
+
 def cpu_baseline(L, host, useful_flops, budget_s=6.0):
     """The oracle as it stands, on a random sample of outputs of each operator,
     sized from a short calibration so that each operator takes about budget_s."""
@@ -272,6 +330,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="only: the three operators over a sweep of invented shapes")
     ap.add_argument("--ablation", action="store_true",
                     help="only: zeros skipped against zeros multiplied, same kernels, on the benchmark layers")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="only: the fp32 matrix rate this box sustains (registers / LDS-fed loop, constant / varying operands)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB -> 1 GiB streaming kernel (calibrates the HBM byte counters)")
     a = ap.parse_args()
@@ -293,6 +353,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe": "torch.mul(src, 1.0, out=dst), float32", "bytes_read_per_launch": 4 * n,
                           "bytes_written_per_launch": 4 * n, "launches": 5}))
+        return
+    if a.mfma_probe:
+        warm_gpu()
+        print(json.dumps({"mfma_probe": mfma_probe(), "unit": "TFLOP/s", "published_peak": PEAK_FP32_MFMA_TFLOPS}))
         return
     if a.sweep or a.ablation:
         warm_gpu()
@@ -328,6 +392,15 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                      "traffic": measured_traffic(a.config, prefix), "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE)",
                      "all_main_kernels": {k: B.useful_flops / v / 1e9 for k, v in mains.items()}},
+    }
+    # the same rate against what the matrix cores sustain here with operands that vary (the published peak
+    # assumes back-to-back issue at 2.4 GHz), and the shader clock while the dominant kernel runs
+    probe = mfma_probe()
+    sustained = probe["lds_fed_k_loop_varying_operands"]["tflops"]
+    line["roofline"]["peak_sustained"] = {
+        "what": "fp32 MFMA rate measured on this box, TFLOP/s: LDS-fed K loop of the general kernels without its global side / registers only; constant / varying operands",
+        "probe": probe, "frac_of_lds_fed_varying": achieved / sustained,
+        "clock_under_dominant_kernel": mfma_probe({"rowrun_gemm<fwd>": B.fwd, "rowrun_gemm<deconv>": B.deconv, "pixel_gemm": B.k_wgrad_main}[dom]),
     }
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(L, B.host, B.useful_flops)

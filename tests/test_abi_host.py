@@ -37,6 +37,25 @@ def test_library_exports_every_declared_symbol(cks):
         assert hasattr(cks, n) or n in ("cks_strerror", "cks_last_hip_error")
 
 
+def test_probe_library_exports_its_header(cks):
+    """The benchmark's measurement probes (include/cks_probe.h -> libcks_probe.so)."""
+    from paper_2306_15951_amd import build
+
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "cks_probe.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(cks_probe_[a-z0-9_]+)\s*\(", text)))
+    assert len(names) == 3
+    if not os.path.exists(build.PROBE_LIB):
+        build.build_lib()
+    L = ctypes.CDLL(build.PROBE_LIB)
+    for n in names:
+        assert hasattr(L, n), n
+    # arguments are checked before anything is launched
+    L.cks_probe_mfma_registers.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    assert L.cks_probe_mfma_registers(None, 1, 1, 0, None) == -2
+    L.cks_probe_mfma_lds.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    assert L.cks_probe_mfma_lds(ctypes.c_void_p(0x1000), 1, 3, 1, 0, None) == -2    # odd chunk count
+
+
 def test_out_dims_and_shape_errors(cks):
     assert cks.cks_out_dims(224, 224, 7, 7, 2, 3) == (112, 112)
     assert cks.cks_out_dims(7, 4, 3, 3, 1, 1) == (7, 4)
