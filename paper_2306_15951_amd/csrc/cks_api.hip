@@ -14,6 +14,7 @@
 #include "cks_patch_fwd.h"
 #include "cks_patch_gemm.h"
 #include "cks_pixel_gemm.h"
+#include "cks_rowrun_dma.h"
 #include "cks_rowrun_gemm.h"
 #include "cks_scatter_deconv.h"
 #include "cks_strip_fwd.h"
@@ -132,12 +133,19 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     const long long kch = OP == OP_FWD ? P.IC : P.OC;
     const long long rowA = OP == OP_FWD ? (long long)P.IH * P.IW * P.IC : (long long)P.OH * P.OW * P.OC;
     const long long rowB = OP == OP_FWD ? (long long)P.FH * P.FW * P.IC : (long long)P.CHp * P.CWp * P.OC;
+    // the 64x64 tile also exists with its chunks loaded straight into LDS (same conditions as the fast loads)
+    constexpr bool kHasDma = BM == 64 && BN == 64 && WM == 2 && WN == 2;
+    const bool dma = kHasDma && !getenv("CKS_TUNE_NO_LDS_DIRECT");
     if constexpr (OP == OP_DECONV_W) {
-        // the caller has checked deconv_in_place_ok: only the fast-load variant exists
+        // the caller has checked deconv_in_place_ok: only the fast-load variants exist
+        if constexpr (kHasDma)
+            if (dma) return launch(rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
         return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
     } else {
         const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (rowB * BN + rowB) * 4 < (1LL << 31) &&
                           !getenv("CKS_TUNE_NO_FAST_LOADS");
+        if constexpr (kHasDma)
+            if (fast && dma) return launch(rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
         if (fast) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
         if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
         return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_SCALAR>, P, (int)blocks, lds, st);

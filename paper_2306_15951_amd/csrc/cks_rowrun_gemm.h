@@ -150,6 +150,46 @@ __device__ inline int banded_work(int bid, const FastDiv &dBand)
     return band * dBand.d + (slot - round * dBand.d);
 }
 
+// Store of a workgroup's tile (shared by the kernels of this file and of cks_rowrun_dma.h).  Every output
+// element of the tile is stored, also when the trimmed range was empty (then it is +0.0).  32 lanes
+// write 128 contiguous bytes.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int TM, int TN>
+__device__ inline void rowrun_store_tile(floatx16 (&acc)[TM][TN], const RowRunParams &P, const RunSet &R, int m0, int n0,
+                                              int wm, int wn, int lane)
+{
+    if (P.bufStore && m0 + BM <= P.N) {
+        // A full tile's rows as one raw buffer: lane part of the offset once, row part as a scalar
+        // offset (which the hardware does not range-check: hence full tiles only), no vector
+        // arithmetic per store.  A column past the channels carries an offset beyond the buffer.
+        const __amdgpu_buffer_rsrc_t rsO = __builtin_amdgcn_make_buffer_rsrc(
+            P.Out + (long)m0 * R.strideO, 0, (int)(BM * R.strideO * 4), 0x00020000);
+        const int so = (int)R.strideO * 4, o0b = (int)R.o0 * 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+                const int voff = col < R.NC ? ((wm * TM + i) * 32 + 4 * (lane >> 5)) * so + col * 4 : (int)0x80000000u;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][r]), rsO, voff,
+                                                          o0b + (8 * (r >> 2) + (r & 3)) * so, 0);
+            }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < P.N && col < R.NC) P.Out[(long)row * R.strideO + R.o0 + col] = acc[i][j][r];
+            }
+        }
+}
+
 // Workgroup tile BM (batch rows) x BN (channels), K-chunk of 32 floats, LDS
 // double-buffered, rows padded to 36 floats so that the 16-byte fragment reads
 // of 32 consecutive rows spread over all banks.  4 waves as WAVES_M x WAVES_N,
@@ -361,39 +401,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
         iteration(t + 1, 1);
     }
 
-    // Every output element of the tile is stored, also when the trimmed range
-    // was empty (then it is +0.0).  32 lanes write 128 contiguous bytes.
-    if (P.bufStore && m0 + BM <= P.N) {
-        // A full tile's rows as one raw buffer: lane part of the offset once, row part as a scalar
-        // offset (which the hardware does not range-check: hence full tiles only), no vector
-        // arithmetic per store.  A column past the channels carries an offset beyond the buffer.
-        const __amdgpu_buffer_rsrc_t rsO = __builtin_amdgcn_make_buffer_rsrc(
-            P.Out + (long)m0 * R.strideO, 0, (int)(BM * R.strideO * 4), 0x00020000);
-        const int so = (int)R.strideO * 4, o0b = (int)R.o0 * 4;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-                const int voff = col < R.NC ? ((wm * TM + i) * 32 + 4 * (lane >> 5)) * so + col * 4 : (int)0x80000000u;
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][r]), rsO, voff,
-                                                          o0b + (8 * (r >> 2) + (r & 3)) * so, 0);
-            }
-        return;
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < P.N && col < R.NC) P.Out[(long)row * R.strideO + R.o0 + col] = acc[i][j][r];
-            }
-        }
+    rowrun_store_tile<BM, BN, WAVES_M, WAVES_N>(acc, P, R, m0, n0, wm, wn, lane);
 }
 
 }  // namespace cks
