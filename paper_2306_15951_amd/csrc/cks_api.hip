@@ -13,6 +13,7 @@
 #include "cks_pack.h"
 #include "cks_patch_fwd.h"
 #include "cks_patch_gemm.h"
+#include "cks_pixel_dma.h"
 #include "cks_pixel_gemm.h"
 #include "cks_rowrun_dma.h"
 #include "cks_rowrun_gemm.h"
@@ -401,6 +402,13 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
     const bool fast = veca && vecb && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
                       (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) &&
                       (P.FH + P.FW + 2) * smax + P.IH + P.IW + P.FH + P.FW < (1LL << 30) && !getenv("CKS_TUNE_NO_FAST_LOADS");
+    if constexpr (BM == 64 && BN == 64 && KC == 16 && WM == 2 && WN == 2 && WK == 1) {
+        // the default tile also exists with its chunks (32 images) loaded straight into LDS
+        if (fast && P.N % kPixelDmaKC == 0 && !getenv("CKS_TUNE_NO_LDS_DIRECT")) {
+            P.dNC = make_fastdiv(P.N / kPixelDmaKC);
+            return launch(pixel_gemm_dma, P, blocks, pixel_dma_lds_bytes(), st);
+        }
+    }
     if (fast) return launch(pixel_gemm_fast<BM, BN, KC, WM, WN, WK>, P, blocks, lds, st);
     if (veca && vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
     if (veca) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
