@@ -470,7 +470,40 @@ __global__ void __launch_bounds__(kThreads) reduce_slices(const float *part, flo
     if (e < elems) {
         const float *p = part + e + (long)zl * elems;
         const long step = (long)ZL * elems;
-        for (int z = zl; z < GZ; z += ZL, p += step) {
+        // eight slices are requested before the first is added (the additions stay in ascending order): a
+        // thread that waited for each load in turn would spend the kernel on memory latency
+        int z = zl;
+        for (; z + 7 * ZL < GZ; z += 8 * ZL, p += 8 * step) {
+            if (VW == 4) {
+                float4 t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = *reinterpret_cast<const float4 *>(p + u * step);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { s[0] += t[u].x; s[VW > 1 ? 1 : 0] += t[u].y; s[VW > 2 ? 2 : 0] += t[u].z; s[VW > 3 ? 3 : 0] += t[u].w; }
+            } else {
+                float t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = p[u * step];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s[0] += t[u];
+            }
+        }
+        for (; z + 3 * ZL < GZ; z += 4 * ZL, p += 4 * step) {
+            if (VW == 4) {
+                float4 t[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) t[u] = *reinterpret_cast<const float4 *>(p + u * step);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { s[0] += t[u].x; s[VW > 1 ? 1 : 0] += t[u].y; s[VW > 2 ? 2 : 0] += t[u].z; s[VW > 3 ? 3 : 0] += t[u].w; }
+            } else {
+                float t[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) t[u] = p[u * step];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) s[0] += t[u];
+            }
+        }
+        for (; z < GZ; z += ZL, p += step) {
             if (VW == 4) {
                 const float4 t = *reinterpret_cast<const float4 *>(p);
                 s[0] += t.x; s[VW > 1 ? 1 : 0] += t.y; s[VW > 2 ? 2 : 0] += t.z; s[VW > 3 ? 3 : 0] += t.w;
