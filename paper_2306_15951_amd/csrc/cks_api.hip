@@ -110,7 +110,9 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     g = g < 1 ? 1 : (g > P.itemsW ? P.itemsW : g);
     const long long bandBlocks = g * P.mTiles * P.nTiles;
     const long long bands = (total + bandBlocks - 1) / bandBlocks;
-    const long long blocks = (bands + kXcds - 1) / kXcds * kXcds * bandBlocks;
+    // (whole groups of 32 workgroups per die: banded_work permutes within them; the surplus workgroups exit at once)
+    const long long perDie = ((bands + kXcds - 1) / kXcds * bandBlocks + 31) / 32 * 32;
+    const long long blocks = perDie * kXcds;
     if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
     P.total = (int)total;
     P.bandBlocks = (int)bandBlocks;
@@ -122,6 +124,7 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     P.dSw = make_fastdiv(P.sw);
     P.pmodsH = P.ph % P.sh;
     P.pmodsW = P.pw % P.sw;
+    P.pairFlip = OP == OP_FWD || (P.sh == 1 && P.sw == 1);
     {
         // output rows of a tile are one image apart
         const long long rowO = OP == OP_FWD ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;

@@ -53,6 +53,7 @@ struct RowRunParams {
     FastDiv dBand, dNT, dMT, dItemsW, dSh, dSw;
     int pmodsH, pmodsW;   // ph mod sh, pw mod sw
     int bufStore;         // the tile's BM output rows span less than 2 GiB: stores go through a buffer descriptor
+    int pairFlip;         // see banded_work
 };
 
 struct RunSet {
@@ -142,9 +143,17 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 // bandBlocks consecutive workgroups (tiles of neighbouring items, which share
 // operands and so that die's L2); bands go to the dies in a serpentine order,
 // so every die gets the same mix of expensive interior and cheap border items.
-__device__ inline int banded_work(int bid, const FastDiv &dBand)
+// Within a die the hardware deals consecutive workgroups to its 32 compute units round-robin (observed:
+// workgroups j and j + 32 of a die share a compute unit), and items are listed expensive first: with `flip`
+// every second group of 32 is walked backwards, so that the workgroups resident together on a compute unit
+// are an expensive and a cheap one rather than two of a kind.  (Not for KS-deconv with several classes: its
+// list is class-major, workgroups 32 apart are neighbouring positions of different classes that read the
+// same dY rows, and sharing a compute unit's cache is worth more there: -12 points on cfg2 when flipped.)
+__device__ inline int banded_work(int bid, const FastDiv &dBand, int flip)
 {
-    const int xcd = bid % kXcds, slot = bid / kXcds;
+    const int xcd = bid % kXcds;
+    int slot = bid / kXcds;
+    if (flip && (slot & 32)) slot ^= 31;
     const int round = fdiv(slot, dBand);
     const int band = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
     return band * dBand.d + (slot - round * dBand.d);
@@ -225,7 +234,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     float *As = smem;                 // [2][BM][LDK]
     float *Bs = smem + 2 * BM * LDK;  // [2][BN][LDK]
 
-    const int work = banded_work(blockIdx.x, P.dBand);
+    const int work = banded_work(blockIdx.x, P.dBand, P.pairFlip);
     if (work >= P.total) return;
     const int wq = fdiv(work, P.dNT), nt = work - wq * P.nTiles;
     const int item = fdiv(wq, P.dMT), mt = wq - item * P.mTiles;
