@@ -26,83 +26,13 @@
 #pragma once
 #include <type_traits>
 
+#include "cks_lds_direct.h"
 #include "cks_rowrun_gemm.h"
 
 namespace cks {
 
 template <int BM, int BN>
 constexpr size_t rowrun_dma_lds_bytes() { return (size_t)2 * (BM + BN) * 32 * sizeof(float); }
-
-typedef float floatx4v __attribute__((ext_vector_type(4)));
-typedef float floatx2v __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) float lds_float_t;
-
-// The assembly exists in the device pass only (the host pass sees the same functions without it: it
-// compiles kernel bodies for their launch stubs and knows no vector-register constraint).
-template <int OFF>
-__device__ __forceinline__ floatx4v lds_read_b128(unsigned addr)
-{
-    static_assert(OFF >= 0 && OFF < 65536, "LDS immediate offset");
-    floatx4v v = {0.f, 0.f, 0.f, 0.f};
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-#else
-    (void)addr;
-#endif
-    return v;
-}
-// two floats OFF0 and OFF1 dwords behind addr (each below 256)
-template <int OFF0, int OFF1>
-__device__ __forceinline__ floatx2v lds_read2_b32(unsigned addr)
-{
-    static_assert(OFF0 >= 0 && OFF0 < 256 && OFF1 >= 0 && OFF1 < 256, "ds_read2 offsets are 8-bit dword counts");
-    floatx2v v = {0.f, 0.f};
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("ds_read2_b32 %0, %1 offset0:%2 offset1:%3" : "=v"(v) : "v"(addr), "n"(OFF0), "n"(OFF1));
-#else
-    (void)addr;
-#endif
-    return v;
-}
-// Wait until at most PENDING LDS reads are in flight.  The values it releases pass through it, so that
-// their consumers are ordered behind the wait.
-template <int PENDING>
-__device__ __forceinline__ void lds_wait(floatx4v &a, floatx4v &b)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(PENDING));
-#endif
-}
-template <int PENDING>
-__device__ __forceinline__ void lds_wait(floatx4v &a, floatx4v &b, floatx4v &c)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(PENDING));
-#endif
-}
-template <int PENDING>
-__device__ __forceinline__ void lds_wait(floatx4v &a, floatx4v &b, floatx4v &c, floatx4v &d)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(PENDING));
-#endif
-}
-// 16 bytes per lane from a raw buffer (byte offset voff per lane + scalar soff) to LDS: the wave's pieces land
-// at dst + 16 * lane; dst must be wave-uniform.
-__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, float *dst, unsigned voff, int soff)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_float_t *)dst, 16, voff, soff, 0, 0);
-#else
-    (void)rsrc; (void)dst; (void)voff; (void)soff;
-#endif
-}
-__device__ __forceinline__ void vmem_wait_all()
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-}
 
 template <int OP, int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P)
