@@ -157,6 +157,14 @@ MID = [
     ("inplace_c_ragged", 40, 100, 7, 7, 160, 3, 3, 1, 1),
     ("inplace_stride_gt_filter", 10, 8, 9, 9, 32, 1, 1, 2, 0),
     ("inplace_4x4_s2_remainder", 9, 12, 10, 9, 64, 4, 4, 2, 1),
+    # the kernels that load their chunks straight into LDS (64x64 tiles, whole 32-float chunks, 16-byte aligned;
+    # filter gradient: batch a multiple of 32): one, two and odd numbers of chunks, ragged batch and channel
+    # tiles, strided classes reading the filter in place
+    ("lds_direct_1x1_one_chunk", 70, 32, 5, 6, 64, 1, 1, 1, 0),
+    ("lds_direct_1x1_two_chunks_oc96", 64, 64, 5, 6, 96, 1, 1, 1, 0),
+    ("lds_direct_s2_classes", 96, 64, 11, 9, 96, 3, 3, 2, 1),
+    ("lds_direct_ragged_columns", 33, 68, 7, 7, 64, 3, 3, 1, 1),
+    ("lds_direct_s3_5x4", 32, 32, 13, 11, 128, 5, 4, 3, 2),
     # more bands than compute units: the input gradient's workgroups take runs of sweep steps that
     # start and end inside bands, and the rows two runs share are added afterwards
     ("stem_row_heads", 37, 3, 24, 224, 64, 7, 7, 2, 3),
