@@ -137,8 +137,9 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     const long long kch = OP == OP_FWD ? P.IC : P.OC;
     const long long rowA = OP == OP_FWD ? (long long)P.IH * P.IW * P.IC : (long long)P.OH * P.OW * P.OC;
     const long long rowB = OP == OP_FWD ? (long long)P.FH * P.FW * P.IC : (long long)P.CHp * P.CWp * P.OC;
-    // the 64x64 tile also exists with its chunks loaded straight into LDS (same conditions as the fast loads)
-    constexpr bool kHasDma = BM == 64 && BN == 64 && WM == 2 && WN == 2;
+    // the default tiles also exist with their chunks loaded straight into LDS (same conditions as the fast loads)
+    constexpr bool kHasDma = (BM == 64 && BN == 64 && WM == 2 && WN == 2) ||
+                             (BM == 128 && BN == 32 && WM == 4 && WN == 1 && OP != OP_DECONV_W);   // (the in-place filter tile is laid out for 64 columns)
     const bool dma = kHasDma && !getenv("CKS_TUNE_NO_LDS_DIRECT");
     if constexpr (OP == OP_DECONV_W) {
         // the caller has checked deconv_in_place_ok: only the fast-load variants exist

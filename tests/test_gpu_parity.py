@@ -165,6 +165,7 @@ MID = [
     ("lds_direct_s2_classes", 96, 64, 11, 9, 96, 3, 3, 2, 1),
     ("lds_direct_ragged_columns", 33, 68, 7, 7, 64, 3, 3, 1, 1),
     ("lds_direct_s3_5x4", 32, 32, 13, 11, 128, 5, 4, 3, 2),
+    ("lds_direct_narrow_output", 130, 32, 9, 9, 40, 3, 3, 1, 1),
     # more bands than compute units: the input gradient's workgroups take runs of sweep steps that
     # start and end inside bands, and the rows two runs share are added afterwards
     ("stem_row_heads", 37, 3, 24, 224, 64, 7, 7, 2, 3),
