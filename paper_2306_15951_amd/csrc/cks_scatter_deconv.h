@@ -60,6 +60,7 @@ constexpr int kScatterLDK = 68;    // K <= 64, +4 keeps 16-row fragments conflic
 constexpr int kScatterPP = 20;     // scratch floats per column: 16 pixels + 4 (bank skew, keeps float4 alignment)
 constexpr int kScatterRP = 128;    // floats per Q row
 constexpr int kScatterMaxTB = 4;   // taps per sub-kernel row and column: ceil(FW / s), ceil(FH / s) <= 4
+constexpr int kScatterStemKeep = 1;   // stem: K groups (of 4) whose filter fragments an MFMA wave keeps in registers
 inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 {
     return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + ((size_t)slots * FH + 1 + 4) * kScatterRP) * sizeof(float);
@@ -71,10 +72,11 @@ inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 // of K group u+1 are requested before the MFMAs of group u are issued and one filter row's gather
 // reads ride along with each group; the few adds fall between MFMAs.  The order is pinned (the
 // compiler would sink every read to its use), and never more than 15 LDS reads are outstanding at
-// a wait, which is all the counter can express.
+// a wait, which is all the counter can express.  The fragments of the first kScatterStemKeep groups
+// never change and stay in registers (wk): a pass starts its MFMAs without waiting for LDS.
 template <int NBH, int NFH, bool MFMAS>
-__device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const float *Bp, const float *const (&gat)[2][kScatterMaxTB],
-                                                  int fhStride, float *qrow, float *Pst)
+__device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const float4 (&wk)[kScatterStemKeep][6], const float *Bp,
+                                                  const float *const (&gat)[2][kScatterMaxTB], int fhStride, float *qrow, float *Pst)
 {
     constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
     float g[NFH][2][MAXTB];
@@ -82,15 +84,20 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
         floatx4 acc[NBH];
 #pragma unroll
         for (int b = 0; b < NBH; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+        constexpr int KEEP = kScatterStemKeep;
+        static_assert(KEEP >= 1 && KEEP <= 3, "the first group's fragments are resident, the last group's are not");
         float4 wc[NBH], wn[NBH];
 #pragma unroll
-        for (int b = 0; b < NBH; ++b) wc[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK);
-        __builtin_amdgcn_sched_group_barrier(0x100, NBH, 0);
+        for (int b = 0; b < NBH; ++b) wc[b] = wk[0][b];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (u < 3) {
+            const bool loads = u < 3 && u + 1 >= KEEP;   // the next group's fragments come from LDS
+            if (loads) {
 #pragma unroll
                 for (int b = 0; b < NBH; ++b) wn[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * (u + 1));
+            } else if (u < 3) {
+#pragma unroll
+                for (int b = 0; b < NBH; ++b) wn[b] = wk[u + 1 < KEEP ? u + 1 : 0][b];
             }
             if (u < NFH) {
 #pragma unroll
@@ -105,7 +112,7 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
                 acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].z, wc[b].z, acc[b], 0, 0, 0);
                 acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].w, wc[b].w, acc[b], 0, 0, 0);
             }
-            if (u < 3) __builtin_amdgcn_sched_group_barrier(0x100, NBH, 0);
+            if (loads) __builtin_amdgcn_sched_group_barrier(0x100, NBH, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
             if (u < NFH) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 4 * NBH - 8, 0);
@@ -158,14 +165,32 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     const int rows4s = 4 * S;
     float *Qdump = Qs + (SLOTS * FH + 1) * RP;   // [4][RP] receives what must go nowhere
 
-    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + (SLOTS * FH + 1 + 4) * RP;
-    for (int i = tid; i < ldsFloats; i += THREADS) smem[i] = 0.f;
+    // All of LDS starts at zero (pad columns, pad slots, the ring); then the filter, transposed.
+    // stem: filter rows 0-3 are columns 0..83, rows 4-6 start at column 96 (one MFMA wave each);
+    // its filter is requested before the zero fill so that the loads are all in flight at once.
+    const int ldsFloats = NB * 16 * LDK + 4 * NB * 16 * PP + (SLOTS * FH + 1 + 4) * RP;   // a multiple of 4
+    constexpr int WREGS = STEM ? (64 * 7 * 7 * 3 + THREADS - 1) / THREADS : 1;
+    float wreg[WREGS];
+    if constexpr (STEM) {
+        const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.W), 0, P.OC * J * 4, 0x00020000);
+#pragma unroll
+        for (int k = 0; k < WREGS; ++k)
+            wreg[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsW, (tid + k * THREADS) * 4, 0, 0));   // past the end: 0
+    }
+    for (int i = tid; i < ldsFloats / 4; i += THREADS) reinterpret_cast<float4 *>(smem)[i] = float4{0.f, 0.f, 0.f, 0.f};
     __syncthreads();
-    for (int i = tid; i < P.OC * J; i += THREADS) {
-        const int oc = i / J, j = i - oc * J;
-        // stem: filter rows 0-3 are columns 0..83, rows 4-6 start at column 96 (one MFMA wave each)
-        const int col = STEM && j >= 4 * L ? j + (96 - 4 * L) : j;
-        Bs[col * LDK + oc] = P.W[i];
+    if constexpr (STEM) {
+#pragma unroll
+        for (int k = 0; k < WREGS; ++k) {
+            const int i = tid + k * THREADS;
+            const int oc = i / J, j = i - oc * J;
+            if (i < P.OC * J) Bs[(j >= 4 * L ? j + (96 - 4 * L) : j) * LDK + oc] = wreg[k];
+        }
+    } else {
+        for (int i = tid; i < P.OC * J; i += THREADS) {
+            const int oc = i / J, j = i - oc * J;
+            Bs[j * LDK + oc] = P.W[i];
+        }
     }
     __syncthreads();
 
@@ -285,6 +310,14 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     const int fhStride = L * PP;
     float *Pst = Pw + lm * PP + 4 * lk;   // + b*16*PP: P[pixels 4lk..4lk+3][column 16b + lm]
     const float *Bp = Bs + (colBase + lm) * LDK + 4 * lk;
+    float4 wk[kScatterStemKeep][6];   // stem: this wave's filter fragments of the first K groups (4 blocks in the second half)
+    if constexpr (STEM) {
+#pragma unroll
+        for (int u = 0; u < kScatterStemKeep; ++u)
+#pragma unroll
+            for (int b = 0; b < 6; ++b)
+                wk[u][b] = (b < 4 || half == 0) ? *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * u) : float4{0.f, 0.f, 0.f, 0.f};
+    }
 
     for (int u = u0; u < u1;) {
         const int band = u / P.nTiles, t0 = u - band * P.nTiles, t1 = min(P.nTiles, t0 + (u1 - u));
@@ -315,13 +348,13 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
 #pragma unroll
                     for (int uu = 0; uu < 4; ++uu) a[uu] = areg[uu];
                     if (i + 1 < t1) fetch(i + 1);   // in flight during this step's MFMAs
-                    if (half == 0) scatter_stem_pass<6, 4, true>(a, Bp, gat, fhStride, qrow, Pst);
-                    else scatter_stem_pass<4, 3, true>(a, Bp, gat, fhStride, qrow, Pst);
+                    if (half == 0) scatter_stem_pass<6, 4, true>(a, wk, Bp, gat, fhStride, qrow, Pst);
+                    else scatter_stem_pass<4, 3, true>(a, wk, Bp, gat, fhStride, qrow, Pst);
                 } else if (i == t1) {
                     // the segment's last dY rows: step 1 on its own
                     float4 a[4];
-                    if (half == 0) scatter_stem_pass<6, 4, false>(a, Bp, gat, fhStride, qrow, Pst);
-                    else scatter_stem_pass<4, 3, false>(a, Bp, gat, fhStride, qrow, Pst);
+                    if (half == 0) scatter_stem_pass<6, 4, false>(a, wk, Bp, gat, fhStride, qrow, Pst);
+                    else scatter_stem_pass<4, 3, false>(a, wk, Bp, gat, fhStride, qrow, Pst);
                 }
                 __syncthreads();
             }
