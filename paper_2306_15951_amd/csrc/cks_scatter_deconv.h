@@ -60,7 +60,8 @@ constexpr int kScatterLDK = 68;    // K <= 64, +4 keeps 16-row fragments conflic
 constexpr int kScatterPP = 20;     // scratch floats per column: 16 pixels + 4 (bank skew, keeps float4 alignment)
 constexpr int kScatterRP = 128;    // floats per Q row
 constexpr int kScatterMaxTB = 4;   // taps per sub-kernel row and column: ceil(FW / s), ceil(FH / s) <= 4
-constexpr int kScatterStemKeep = 1;   // stem: K groups (of 4) whose filter fragments an MFMA wave keeps in registers
+constexpr int kScatterStemSlots = 16;  // stem: depth of the Q ring (11 rows are needed; a power of two makes the slot a mask)
+constexpr int kScatterStemKeep = 2;   // stem: K groups (of 4) whose filter fragments an MFMA wave keeps in registers
 inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 {
     return ((size_t)NB * 16 * kScatterLDK + (size_t)4 * NB * 16 * kScatterPP + ((size_t)slots * FH + 1 + 4) * kScatterRP) * sizeof(float);
@@ -70,16 +71,22 @@ inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 // row, and step 1 for NFH filter rows of the row it computed in the previous pass (that P is still
 // in the wave's scratch, which is overwritten only at the end of this pass).  The filter fragments
 // of K group u+1 are requested before the MFMAs of group u are issued and one filter row's gather
-// reads ride along with each group; the few adds fall between MFMAs.  The order is pinned (the
-// compiler would sink every read to its use), and never more than 15 LDS reads are outstanding at
-// a wait, which is all the counter can express.  The fragments of the first kScatterStemKeep groups
+// reads ride along with each group and are summed and written during the next one.  The order is
+// pinned (the compiler would sink every read to its use), and never more than 15 LDS reads are
+// outstanding at a wait, which is all the counter can express.  The fragments of the first kScatterStemKeep groups
 // never change and stay in registers (wk): a pass starts its MFMAs without waiting for LDS.
+//
+// Step 1 on the stem: lane l of gather q takes pixel column 2v + q (v = l / 3) and channel l mod 3,
+// so that its taps tb = 0 .. 3 - q sit at gs[q] + tb * (6 PP - 1) + fh * 21 PP: one lane constant,
+// the rest immediates, and the 64 lanes of a read fall into 64 different banks.  A tap that reaches
+// before pixel 0 or past pixel 15 of its column lands in pad slots, which stay zero.  The sum goes
+// to position 64 q + l of the Q row.
 template <int NBH, int NFH, bool MFMAS>
 __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const float4 (&wk)[kScatterStemKeep][6], const float *Bp,
-                                                  const float *const (&gat)[2][kScatterMaxTB], int fhStride, float *qrow, float *Pst)
+                                                  const float *const (&gs)[2], float *qrow, float *Pst)
 {
     constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
-    float g[NFH][2][MAXTB];
+    constexpr int TAP = 6 * PP - 1, FHS = 21 * PP;   // scratch floats from one tap / filter row to the next
     if constexpr (MFMAS) {
         floatx4 acc[NBH];
 #pragma unroll
@@ -87,11 +94,13 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
         constexpr int KEEP = kScatterStemKeep;
         static_assert(KEEP >= 1 && KEEP <= 3, "the first group's fragments are resident, the last group's are not");
         float4 wc[NBH], wn[NBH];
+        float g[2][MAXTB];   // the addends of one filter row: summed and written during the next group
 #pragma unroll
         for (int b = 0; b < NBH; ++b) wc[b] = wk[0][b];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const bool loads = u < 3 && u + 1 >= KEEP;   // the next group's fragments come from LDS
+            const bool sums = u >= 1 && u - 1 < NFH, gathers = u < NFH;
             if (loads) {
 #pragma unroll
                 for (int b = 0; b < NBH; ++b) wn[b] = *reinterpret_cast<const float4 *>(Bp + b * 16 * LDK + 16 * (u + 1));
@@ -99,11 +108,15 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
 #pragma unroll
                 for (int b = 0; b < NBH; ++b) wn[b] = wk[u + 1 < KEEP ? u + 1 : 0][b];
             }
-            if (u < NFH) {
+            if (sums) {
+                qrow[(u - 1) * RP] = (g[0][0] + g[0][1]) + (g[0][2] + g[0][3]);
+                qrow[(u - 1) * RP + 64] = (g[1][0] + g[1][1]) + g[1][2];
+            }
+            if (gathers) {
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
 #pragma unroll
-                    for (int tb = 0; tb < MAXTB; ++tb) g[u][q][tb] = gat[q][tb][u * fhStride];
+                    for (int tb = 0; tb < MAXTB - q; ++tb) g[q][tb] = gs[q][tb * TAP + u * FHS];
             }
 #pragma unroll
             for (int b = 0; b < NBH; ++b) {
@@ -114,31 +127,35 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
             }
             if (loads) __builtin_amdgcn_sched_group_barrier(0x100, NBH, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-            if (u < NFH) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB, 0);
+            if (sums) {
+                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
+            }
+            if (gathers) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MAXTB - 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 4 * NBH - 8, 0);
 #pragma unroll
             for (int b = 0; b < NBH; ++b) wc[b] = wn[b];
         }
-#pragma unroll
-        for (int fh = 0; fh < NFH; ++fh)
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-                qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+        if constexpr (NFH == 4) {
+            qrow[3 * RP] = (g[0][0] + g[0][1]) + (g[0][2] + g[0][3]);
+            qrow[3 * RP + 64] = (g[1][0] + g[1][1]) + g[1][2];
+        }
 #pragma unroll
         for (int b = 0; b < NBH; ++b)
             *reinterpret_cast<float4 *>(Pst + b * 16 * PP) = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
     } else {
+        float g[NFH][2][MAXTB];
 #pragma unroll
         for (int fh = 0; fh < NFH; ++fh)
 #pragma unroll
             for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int tb = 0; tb < MAXTB; ++tb) g[fh][q][tb] = gat[q][tb][fh * fhStride];
+                for (int tb = 0; tb < MAXTB - q; ++tb) g[fh][q][tb] = gs[q][tb * TAP + fh * FHS];
 #pragma unroll
-        for (int fh = 0; fh < NFH; ++fh)
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-                qrow[fh * RP + 64 * q] = (g[fh][q][0] + g[fh][q][1]) + (g[fh][q][2] + g[fh][q][3]);
+        for (int fh = 0; fh < NFH; ++fh) {
+            qrow[fh * RP] = (g[fh][0][0] + g[fh][0][1]) + (g[fh][0][2] + g[fh][0][3]);
+            qrow[fh * RP + 64] = (g[fh][1][0] + g[fh][1][1]) + g[fh][1][2];
+        }
     }
 }
 
@@ -152,7 +169,7 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     constexpr int LDK = kScatterLDK, PP = kScatterPP, RP = kScatterRP, MAXTB = kScatterMaxTB;
     constexpr int kBeyond = (int)0x80000000u;   // an offset outside every descriptor used here
     const int FH = STEM ? 7 : P.FH, FW = STEM ? 7 : P.FW, IC = STEM ? 3 : P.IC, S = STEM ? 2 : P.s;
-    const int SLOTS = STEM ? 11 : P.slots;   // 8 + (FH-1)/s
+    const int SLOTS = STEM ? kScatterStemSlots : P.slots;
     extern __shared__ __align__(16) float smem[];
     float *Bs = smem;                           // [NB*16][LDK]       filter, column-major: Bs[j'][oc]
     float *Ps = Bs + NB * 16 * LDK;             // [4][NB*16][PP]     per-wave P scratch
@@ -220,7 +237,9 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
             int voffX[2], voffH[2], voffR[2];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                const int x = lane + 64 * q;
+                // position lane + 64 q of a Q row is float x of the band's dX row; the stem's Q rows are
+                // ordered by column parity (see scatter_stem_pass)
+                const int x = STEM ? 6 * (lane / 3) + 3 * q + lane % 3 : lane + 64 * q;
                 const bool inrow = x < sw && x0 + x >= 0 && x0 + x < rowFloats;
                 voffX[q] = (inrow && !(c > 0 && x < P.OVF)) ? (x0 + x) * 4 : kBeyond;
                 voffH[q] = (c > 0 && x < P.OVF) ? x * 4 : kBeyond;
@@ -236,9 +255,37 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
             const int rowBeg = t0 * rows4s, rowEnd = last ? P.nFlush * rows4s : t1 * rows4s + P.HR;
             const int kEnd = (rowEnd + rows4s - 1) / rows4s;
             const int ohBeg = 4 * t0, ohEnd = min(P.OH, 4 * t1);
+            // stem: output steps whose 8 rows all lie in the image and draw on dY rows of this segment
+            // only (4k-3 .. 4k+3) need none of the checks below
+            const int kFirst = max(t0 + 1, (P.p + 7) / 8);   // row 8k - p is not above the image
+            const int kPlain = STEM ? min(t1, P.IH + P.p >= 8 ? (P.IH + P.p - 8) / 8 + 1 : 0) : 0;   // row 8k + 7 - p not below it
             for (int i = t0; i < kEnd + DELAY; ++i) {
                 const int k = i - DELAY;   // rows [k*4s, (k+1)*4s) are complete once step 1 of tile k is done
-                if (k >= t0) {
+                if (STEM && k >= kFirst && k < kPlain) {
+                    float v0[2][MAXTB], v1[2][MAXTB];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {   // rows 8k + pw and 8k + pw + 4 = oh*2 + fh: fh = (pw & 1) + 2t, oh = 4k + pw/2 + 2j - t
+#pragma unroll
+                        for (int t = 0; t < MAXTB; ++t) {
+                            const int fh = (pw & 1) + 2 * t, slot = (4 * k + (pw >> 1) + 2 * j - t) & (kScatterStemSlots - 1);
+                            const float *qp = (fh < 7 ? Qs + (slot * 7 + fh) * RP : Qzero) + lane;
+                            v0[j][t] = qp[0];
+                            v1[j][t] = qp[64];
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int soff = (8 * k + pw + 4 * j - P.p) * rowFloats * 4, soffH = (8 * k + pw + 4 * j - P.p) * P.OVF * 4;
+                        const float sum0 = (v0[j][0] + v0[j][1]) + (v0[j][2] + v0[j][3]);
+                        const float sum1 = (v1[j][0] + v1[j][1]) + (v1[j][2] + v1[j][3]);
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsX, voffX[0], soff, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsX, voffX[1], soff, 0);
+                        if (c > 0) {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum0), rsH, voffH[0], soffH, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sum1), rsH, voffH[1], soffH, 0);
+                        }
+                    }
+                } else if (k >= t0) {
 #pragma unroll 2
                     for (int r = pw; r < rows4s; r += 4) {
                         const int row = k * rows4s + r;   // = ih + p
@@ -293,21 +340,30 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     float4 areg[4];
     // step 1, lane constants: ring float x = lane + 64q is pixel column pwx = x / IC (= v*s + b), channel ic
     float *Pw = Ps + (wrow * NB * 16 + colBase) * PP;   // this wave's columns of its row's scratch
-    const float *gat[2][MAXTB];
-    const int touched = (15 * S + FW) * IC;
+    const float *gat[2][MAXTB];   // general geometry: one address per tap
+    const float *gs[2];           // stem: one address per gather, see scatter_stem_pass
+    const int fhStride = L * PP;
+    if constexpr (STEM) {
+        // lanes past the last pixel column (l >= 57 / 54) sit at "pixel 19", from where every tap
+        // reads a pad slot: their Q positions (dX floats no pixel reaches) hold zeros
+        const int v = min(lane / 3, 19), ic = lane % 3;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int x = lane + 64 * q;
-        const int pwx = x / IC, ic = x - pwx * IC, b = pwx % S, v = pwx / S;
+        for (int q = 0; q < 2; ++q) gs[q] = Pw + (3 * q + ic) * PP + v;
+    } else {
+        const int touched = (15 * S + FW) * IC;
 #pragma unroll
-        for (int tb = 0; tb < MAXTB; ++tb) {
-            // column (fh=0, fw=b+s*tb, ic), pixel v-tb; + fh*L*PP selects the filter row.  A tap that does
-            // not exist reads pad slot 16 of column fh*L instead, which is never written and stays zero.
-            const bool ok = x < touched && b + S * tb < FW && v - tb >= 0 && v - tb < 16;
-            gat[q][tb] = ok ? Pw + ((b + S * tb) * IC + ic) * PP + v - tb : Pw + 16;
+        for (int q = 0; q < 2; ++q) {
+            const int x = lane + 64 * q;
+            const int pwx = x / IC, ic = x - pwx * IC, b = pwx % S, v = pwx / S;
+#pragma unroll
+            for (int tb = 0; tb < MAXTB; ++tb) {
+                // column (fh=0, fw=b+s*tb, ic), pixel v-tb; + fh*L*PP selects the filter row.  A tap that does
+                // not exist reads pad slot 16 of column fh*L instead, which is never written and stays zero.
+                const bool ok = x < touched && b + S * tb < FW && v - tb >= 0 && v - tb < 16;
+                gat[q][tb] = ok ? Pw + ((b + S * tb) * IC + ic) * PP + v - tb : Pw + 16;
+            }
         }
     }
-    const int fhStride = L * PP;
     float *Pst = Pw + lm * PP + 4 * lk;   // + b*16*PP: P[pixels 4lk..4lk+3][column 16b + lm]
     const float *Bp = Bs + (colBase + lm) * LDK + 4 * lk;
     float4 wk[kScatterStemKeep][6];   // stem: this wave's filter fragments of the first K groups (4 blocks in the second half)
@@ -348,13 +404,13 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
 #pragma unroll
                     for (int uu = 0; uu < 4; ++uu) a[uu] = areg[uu];
                     if (i + 1 < t1) fetch(i + 1);   // in flight during this step's MFMAs
-                    if (half == 0) scatter_stem_pass<6, 4, true>(a, wk, Bp, gat, fhStride, qrow, Pst);
-                    else scatter_stem_pass<4, 3, true>(a, wk, Bp, gat, fhStride, qrow, Pst);
+                    if (half == 0) scatter_stem_pass<6, 4, true>(a, wk, Bp, gs, qrow, Pst);
+                    else scatter_stem_pass<4, 3, true>(a, wk, Bp, gs, qrow, Pst);
                 } else if (i == t1) {
                     // the segment's last dY rows: step 1 on its own
                     float4 a[4];
-                    if (half == 0) scatter_stem_pass<6, 4, false>(a, wk, Bp, gat, fhStride, qrow, Pst);
-                    else scatter_stem_pass<4, 3, false>(a, wk, Bp, gat, fhStride, qrow, Pst);
+                    if (half == 0) scatter_stem_pass<6, 4, false>(a, wk, Bp, gs, qrow, Pst);
+                    else scatter_stem_pass<4, 3, false>(a, wk, Bp, gs, qrow, Pst);
                 }
                 __syncthreads();
             }

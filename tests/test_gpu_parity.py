@@ -146,6 +146,12 @@ MID = [
     ("stem_pad5_tiny", 3, 3, 7, 9, 12, 7, 7, 2, 5),
     ("stem_remainder_rows", 2, 3, 32, 31, 64, 7, 7, 2, 3),
     ("stem_single_pixel_rows", 1, 3, 9, 130, 64, 7, 7, 2, 3),
+    # the stem input gradient's check-free output steps start and end by padding and image height; with
+    # padding 0 and width 38 the last band's row has three floats that no pixel reaches
+    ("stem_oc64_pad0_unreached_columns", 2, 3, 75, 38, 64, 7, 7, 2, 0),
+    ("stem_oc64_pad6", 2, 3, 44, 45, 64, 7, 7, 2, 6),
+    ("stem_oc64_pad9_tall", 1, 3, 61, 26, 64, 7, 7, 2, 9),
+    ("stem_oc64_pad20", 1, 3, 40, 20, 64, 7, 7, 2, 20),
     ("rgb_3x3", 6, 3, 20, 21, 16, 3, 3, 1, 1),
     ("rgb_5x5_s2", 4, 3, 19, 40, 32, 5, 5, 2, 2),
     ("rgb_4x4_s3", 3, 3, 17, 35, 8, 4, 4, 3, 1),
