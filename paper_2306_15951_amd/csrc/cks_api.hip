@@ -486,7 +486,7 @@ ScatterPlan plan_scatter(const Geo &g)
     P.KP = (OC + 15) / 16 * 16;
     S.NB = J <= 64 ? 4 : 10;
     if (scatter_deconv_lds_bytes(S.NB, P.slots, FH) > 160 * 1024) return S;
-    if (!fits_i31((long long)N * P.nBands * H) || P.OVF > kThreads) return S;   // add_band_heads indexes rows with 32 bits
+    if (!fits_i31((long long)N * P.nBands * H) || P.OVF > kThreads) return S;   // add_heads indexes rows with 32 bits
     const long long steps = (long long)N * P.nBands * P.nTiles;
     if (!fits_i31(steps)) return S;
     P.steps = (int)steps;
@@ -604,25 +604,24 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
         else if (stem) rc = launch(scatter_deconv<10, true>, S.P, S.blocks, lds, st, kScatterStemThreads);
         else rc = launch(scatter_deconv<10, false>, S.P, S.blocks, lds, st, kScatterThreads);
         if (rc != CKS_OK) return rc;
-        if (S.P.nBands > 1 && S.P.OVF > 0) {
-            BandHeadParams B{};
-            B.head = (const float *)ws; B.dX = dX;
-            B.N = N; B.IC = C; B.IH = H; B.IW = W; B.s = stride; B.p = padding; B.nBands = S.P.nBands; B.OVF = S.P.OVF;
-            const long long rows = (long long)N * (S.P.nBands - 1) * H;   // plan_scatter has checked that this fits 31 bits
-            B.rows = (int)rows;
-            B.xw = 1;
-            while (B.xw < S.P.OVF) B.xw *= 2;
-            const int rpb = kThreads / B.xw;
-            rc = launch(add_band_heads, B, (int)((rows + rpb - 1) / rpb), 0, st);
-            if (rc != CKS_OK) return rc;
-        }
-        if (S.rowheadBytes) {
-            RowHeadParams R{};
-            R.rowhead = S.P.rowhead; R.dX = dX;
-            R.N = N; R.IC = C; R.IH = H; R.IW = W; R.s = stride; R.p = padding; R.nBands = S.P.nBands; R.nTiles = S.P.nTiles;
-            R.SW = S.P.SW; R.SWlast = S.P.SWlast; R.HR = S.P.HR; R.stepsPerBlock = S.P.stepsPerBlock; R.blocks = S.blocks;
+        const bool bandPart = S.P.nBands > 1 && S.P.OVF > 0;
+        if (bandPart || S.rowheadBytes) {
+            HeadsParams B{};
+            B.head = (const float *)ws; B.rowhead = S.rowheadBytes ? S.P.rowhead : nullptr; B.dX = dX;
+            B.N = N; B.IC = C; B.IH = H; B.IW = W; B.s = stride; B.p = padding; B.nBands = S.P.nBands; B.nTiles = S.P.nTiles;
+            B.OVF = S.P.OVF; B.SW = S.P.SW; B.SWlast = S.P.SWlast; B.HR = S.P.HR; B.stepsPerBlock = S.P.stepsPerBlock; B.blocks = S.blocks;
+            while ((kHeadFloats << B.xwShift) < S.P.OVF) ++B.xwShift;   // OVF <= 256 floats (plan_scatter): at most a workgroup
+            B.dIH = make_fastdiv(H); B.dBandsLeft = make_fastdiv(S.P.nBands > 1 ? S.P.nBands - 1 : 1); B.dSteps = make_fastdiv(S.P.stepsPerBlock);
+            if (bandPart) {
+                const long long rows = (long long)N * (S.P.nBands - 1) * H;   // plan_scatter has checked that this fits 31 bits
+                const long long rpb = kThreads >> B.xwShift;
+                B.rows = (int)rows;
+                B.bandBlocks = (int)((rows + rpb - 1) / rpb);
+            }
             const int per = kThreads / kScatterRP;
-            rc = launch(add_row_heads, R, (S.blocks * S.P.HR + per - 1) / per, 0, st);
+            const long long rowBlocks = S.rowheadBytes ? ((long long)S.blocks * S.P.HR + per - 1) / per : 0;
+            if (!fits_i31(B.bandBlocks + rowBlocks)) return CKS_ERR_SHAPE;
+            rc = launch(add_heads, B, (int)(B.bandBlocks + rowBlocks), 0, st);
         }
         return rc;
     }

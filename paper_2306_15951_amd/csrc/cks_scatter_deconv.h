@@ -20,7 +20,7 @@
 // A workgroup owns one image and a band of 16 dY columns and sweeps it top to
 // bottom, four dY rows (one per MFMA wave) per step.  Neighbouring bands overlap
 // in (FW - s) dX pixel columns: a band writes its share of the columns it has in
-// common with its left neighbour to a small side buffer, and add_band_heads adds
+// common with its left neighbour to a small side buffer, and add_heads adds
 // that to dX afterwards, so no two workgroups ever add to one address.
 //
 // Every global access is a buffer access "lane constant + scalar" against a
@@ -458,40 +458,67 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     }
 }
 
-// dX[n, ih, (16 c s - p)*IC + x] += head[n][c-1][ih][x] for every band c >= 1.
-struct BandHeadParams {
+// What the side buffers hold is added to dX by one launch, every dX element by one thread:
+//   band part: dX[n, ih, (16 c s - p)*IC + x] += head[n][c-1][ih][x] for every band c >= 1, x < OVF;
+//   row part:  dX rows [4 t0 s, 4 t0 s + HR) of the band a workgroup's first segment lies in += that
+//              workgroup's rowhead, if the segment starts inside the band.
+// Where a row head crosses the columns that two bands share, the band part's thread adds it as
+// well (after head) and the row part leaves those columns alone.  The host has checked
+// that at most one workgroup starts inside a band and that no two row heads meet in a dX element.
+constexpr int kHeadFloats = 1;   // measured: more floats per thread (fewer, longer threads) is slower
+struct HeadsParams {
     const float *head;
+    const float *rowhead;   // null: no workgroup starts inside a band
     float *dX;
-    int N, IC, IH, IW, s, p, nBands, OVF;
-    int rows;     // N * (nBands-1) * IH rows of OVF floats
-    int xw;       // threads per row: power of two >= OVF, <= 256
+    int N, IC, IH, IW, s, p, nBands, nTiles, OVF, SW, SWlast, HR, stepsPerBlock, blocks;
+    int rows;         // band part: N * (nBands-1) * IH rows of OVF floats (0 if there is no band part)
+    int xwShift;      // a row is shared by 2^xwShift threads, kHeadFloats consecutive floats each
+    int bandBlocks;   // workgroups of the band part; the row part's follow
+    FastDiv dIH, dBandsLeft, dSteps;   // IH, nBands - 1, stepsPerBlock
 };
 
-__global__ void __launch_bounds__(kThreads) add_band_heads(const BandHeadParams P)
+__global__ void __launch_bounds__(kThreads) add_heads(const HeadsParams P)
 {
-    const int rpb = kThreads / P.xw;   // rows per workgroup
-    const int row = blockIdx.x * rpb + threadIdx.x / P.xw, x = threadIdx.x % P.xw;
-    if (row >= P.rows || x >= P.OVF) return;
-    const int ih = row % P.IH, t = row / P.IH;
-    const int c = t % (P.nBands - 1) + 1, n = t / (P.nBands - 1);
-    const int col = (16 * c * P.s - P.p) * P.IC + x;
-    if (col < 0 || col >= P.IW * P.IC) return;
-    P.dX[((long)n * P.IH + ih) * P.IW * P.IC + col] += P.head[(long)row * P.OVF + x];
-}
-
-// dX rows [4 t0 s, 4 t0 s + HR) of the band a workgroup's first segment lies in += that workgroup's
-// rowhead (if the segment starts inside the band).  The host has checked that no two workgroups'
-// row heads meet in one dX element, so every element is added to by one thread only.
-struct RowHeadParams {
-    const float *rowhead;
-    float *dX;
-    int N, IC, IH, IW, s, p, nBands, nTiles, SW, SWlast, HR, stepsPerBlock, blocks;
-};
-
-__global__ void __launch_bounds__(kThreads) add_row_heads(const RowHeadParams P)
-{
-    const int per = kThreads / kScatterRP;   // rows per workgroup of this kernel
-    const int hr = blockIdx.x * per + threadIdx.x / kScatterRP, x = threadIdx.x % kScatterRP;
+    const int rowFloats = P.IW * P.IC;
+    if ((int)blockIdx.x < P.bandBlocks) {
+        const int row = blockIdx.x * (kThreads >> P.xwShift) + (threadIdx.x >> P.xwShift), x0 = (threadIdx.x & ((1 << P.xwShift) - 1)) * kHeadFloats;
+        if (row >= P.rows || x0 >= P.OVF) return;
+        const int t = fdiv(row, P.dIH), ih = row - t * P.IH;
+        const int n = fdiv(t, P.dBandsLeft), c = t - n * (P.nBands - 1) + 1;
+        const int col0 = (16 * c * P.s - P.p) * P.IC + x0;
+        // row heads that cross these columns: of the workgroup that starts inside this band (from its
+        // float 0) and of the one that starts inside the left neighbour (from its float 16 s IC)
+        const float *rh[2] = {nullptr, nullptr};
+        if (P.rowhead) {
+#pragma unroll
+            for (int side = 0; side < 2; ++side) {
+                const int first = (n * P.nBands + c - side) * P.nTiles, g = fdiv(first, P.dSteps) + 1;   // first run starting after the band's first step
+                if (g >= P.blocks) continue;
+                const int t0 = g * P.stepsPerBlock - first, r = ih + P.p - t0 * 4 * P.s;
+                if (t0 < P.nTiles && r >= 0 && r < P.HR) rh[side] = P.rowhead + ((long)g * P.HR + r) * kScatterRP + side * 16 * P.s * P.IC;
+            }
+        }
+        const float *hp = P.head + (long)row * P.OVF;
+        float *dp = P.dX + ((long)n * P.IH + ih) * rowFloats;
+        // every load before the first store: the compiler cannot know that the buffers are distinct
+        float v[kHeadFloats], d[kHeadFloats];
+        bool ok[kHeadFloats];
+#pragma unroll
+        for (int j = 0; j < kHeadFloats; ++j) {
+            const int x = x0 + j, col = col0 + j;
+            ok[j] = x < P.OVF && col >= 0 && col < rowFloats;
+            v[j] = ok[j] ? hp[x] : 0.f;
+            d[j] = ok[j] ? dp[col] : 0.f;
+            if (ok[j] && rh[0]) v[j] += rh[0][x];
+            if (ok[j] && rh[1]) v[j] += rh[1][x];
+        }
+#pragma unroll
+        for (int j = 0; j < kHeadFloats; ++j)
+            if (ok[j]) dp[col0 + j] = d[j] + v[j];
+        return;
+    }
+    const int per = kThreads / kScatterRP;   // rows per workgroup
+    const int hr = (blockIdx.x - P.bandBlocks) * per + threadIdx.x / kScatterRP, x = threadIdx.x % kScatterRP;
     if (hr >= P.blocks * P.HR) return;
     const int g = hr / P.HR, r = hr - g * P.HR;
     const int u0 = g * P.stepsPerBlock;
@@ -501,8 +528,9 @@ __global__ void __launch_bounds__(kThreads) add_row_heads(const RowHeadParams P)
     const int ih = t0 * 4 * P.s + r - P.p;
     const int sw = c == P.nBands - 1 ? P.SWlast : P.SW;
     const int col = (16 * c * P.s - P.p) * P.IC + x;
-    if (ih < 0 || ih >= P.IH || x >= sw || col < 0 || col >= P.IW * P.IC) return;
-    P.dX[((long)n * P.IH + ih) * P.IW * P.IC + col] += P.rowhead[(long)hr * kScatterRP + x];
+    if (ih < 0 || ih >= P.IH || x >= sw || col < 0 || col >= rowFloats) return;
+    if (P.OVF > 0 && ((c > 0 && x < P.OVF) || (c < P.nBands - 1 && x >= 16 * P.s * P.IC))) return;   // the band part's
+    P.dX[((long)n * P.IH + ih) * rowFloats + col] += P.rowhead[(long)hr * kScatterRP + x];
 }
 
 }  // namespace cks
