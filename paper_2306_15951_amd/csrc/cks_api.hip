@@ -595,8 +595,7 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
         const int stride = g.sh, padding = g.ph;   // the same on both axes (plan_scatter)
         S.P.dY = dY; S.P.W = Wt; S.P.dX = dX; S.P.head = (float *)ws;
         S.P.rowhead = (float *)((char *)ws + S.headBytes);
-        // the stem kernel orders a band's row by column parity, 63 floats of each: the last band's row may not be longer
-        const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2 && OC == 64 && S.P.SWlast <= 126;
+        const bool stem = FH == 7 && FW == 7 && C == 3 && stride == 2 && OC == 64;
         if (stem) S.P.slots = kScatterStemSlots;
         const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
         int rc;

@@ -79,8 +79,8 @@ inline size_t scatter_deconv_lds_bytes(int NB, int slots, int FH)
 // Step 1 on the stem: lane l of gather q takes pixel column 2v + q (v = l / 3) and channel l mod 3,
 // so that its taps tb = 0 .. 3 - q sit at gs[q] + tb * (6 PP - 1) + fh * 21 PP: one lane constant,
 // the rest immediates, and the 64 lanes of a read fall into 64 different banks.  A tap that reaches
-// before pixel 0 or past pixel 15 of its column lands in pad slots, which stay zero.  The sum goes
-// to position 64 q + l of the Q row.
+// before pixel 0 or past pixel 15 of its column lands in pad slots, which stay zero.  The sum is
+// float 6v + 3q + l mod 3 of the Q row (qrow points at float 6v + l mod 3).
 template <int NBH, int NFH, bool MFMAS>
 __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const float4 (&wk)[kScatterStemKeep][6], const float *Bp,
                                                   const float *const (&gs)[2], float *qrow, float *Pst)
@@ -110,7 +110,7 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
             }
             if (sums) {
                 qrow[(u - 1) * RP] = (g[0][0] + g[0][1]) + (g[0][2] + g[0][3]);
-                qrow[(u - 1) * RP + 64] = (g[1][0] + g[1][1]) + g[1][2];
+                qrow[(u - 1) * RP + 3] = (g[1][0] + g[1][1]) + g[1][2];
             }
             if (gathers) {
 #pragma unroll
@@ -138,7 +138,7 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
         }
         if constexpr (NFH == 4) {
             qrow[3 * RP] = (g[0][0] + g[0][1]) + (g[0][2] + g[0][3]);
-            qrow[3 * RP + 64] = (g[1][0] + g[1][1]) + g[1][2];
+            qrow[3 * RP + 3] = (g[1][0] + g[1][1]) + g[1][2];
         }
 #pragma unroll
         for (int b = 0; b < NBH; ++b)
@@ -154,7 +154,7 @@ __device__ __forceinline__ void scatter_stem_pass(const float4 (&a)[4], const fl
 #pragma unroll
         for (int fh = 0; fh < NFH; ++fh) {
             qrow[fh * RP] = (g[fh][0][0] + g[fh][0][1]) + (g[fh][0][2] + g[fh][0][3]);
-            qrow[fh * RP + 64] = (g[fh][1][0] + g[fh][1][1]) + g[fh][1][2];
+            qrow[fh * RP + 3] = (g[fh][1][0] + g[fh][1][1]) + g[fh][1][2];
         }
     }
 }
@@ -237,9 +237,7 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
             int voffX[2], voffH[2], voffR[2];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                // position lane + 64 q of a Q row is float x of the band's dX row; the stem's Q rows are
-                // ordered by column parity (see scatter_stem_pass)
-                const int x = STEM ? 6 * (lane / 3) + 3 * q + lane % 3 : lane + 64 * q;
+                const int x = lane + 64 * q;
                 const bool inrow = x < sw && x0 + x >= 0 && x0 + x < rowFloats;
                 voffX[q] = (inrow && !(c > 0 && x < P.OVF)) ? (x0 + x) * 4 : kBeyond;
                 voffH[q] = (c > 0 && x < P.OVF) ? x * 4 : kBeyond;
@@ -342,6 +340,7 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
     float *Pw = Ps + (wrow * NB * 16 + colBase) * PP;   // this wave's columns of its row's scratch
     const float *gat[2][MAXTB];   // general geometry: one address per tap
     const float *gs[2];           // stem: one address per gather, see scatter_stem_pass
+    int qx = lane;                // stem: the Q row float of this lane's first gather
     const int fhStride = L * PP;
     if constexpr (STEM) {
         // lanes past the last pixel column (l >= 57 / 54) sit at "pixel 19", from where every tap
@@ -349,6 +348,7 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
         const int v = min(lane / 3, 19), ic = lane % 3;
 #pragma unroll
         for (int q = 0; q < 2; ++q) gs[q] = Pw + (3 * q + ic) * PP + v;
+        qx = 6 * v + ic;   // <= 116: the idle lanes all write their zeros to floats 114 .. 119
     } else {
         const int touched = (15 * S + FW) * IC;
 #pragma unroll
@@ -398,7 +398,7 @@ __global__ void __launch_bounds__(STEM ? kScatterStemThreads : kScatterThreads) 
             for (int i = t0; i < kEnd + DELAY; ++i) {
                 // Q rows of dY row 4(i-1) + wrow.  In a segment's first pass the scratch holds nothing of
                 // this segment: what is gathered goes to the dump row.
-                float *qrow = (i > t0 ? Qs + (((4 * (i - 1) + wrow) % SLOTS) * 7 + fhBase) * RP : Qdump) + lane;
+                float *qrow = (i > t0 ? Qs + (((4 * (i - 1) + wrow) % SLOTS) * 7 + fhBase) * RP : Qdump) + qx;
                 if (i < t1) {   // uniform
                     float4 a[4];
 #pragma unroll
