@@ -69,7 +69,7 @@ struct StripStager {
     static constexpr int RROWS = G::SRA / 4;
     static constexpr int kBeyond = (int)0x80000000u;
     float v[RROWS][G::PASSES];
-    int voff[G::PASSES];
+    int voff[G::PASSES], vlast[G::PASSES];   // byte offsets of this lane's floats in an image row; the same for the wave's last row
     int band = -1;
 
     // tile = (image n, band c of 16 output columns, row tile t of 4 output rows); all wave-uniform
@@ -83,21 +83,22 @@ struct StripStager {
             for (int q = 0; q < G::PASSES; ++q) {
                 const int x = lane + 64 * q;
                 voff[q] = (x < G::SWF && x0 + x >= 0 && x0 + x < rowFloats) ? (x0 + x) * 4 : kBeyond;
+                vlast[q] = pw + 4 * (RROWS - 1) < G::SR ? voff[q] : kBeyond;   // (the rows past SR exist in LDS only)
             }
         }
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float *>(X) + (long)n * IH * rowFloats, 0, IH * rowFloats * 4, 0x00020000);
         const int ih0 = 4 * t * G::S_ - p, rowB = rowFloats * 4;
+        static_assert(4 * (RROWS - 1) < G::SR, "only a wave's last row can lie past the strip");
         if (ih0 >= 0 && ih0 + G::SR <= IH) {
+            // straight-line: a lane that has nothing to fetch carries an offset beyond the image, and the
+            // range check looks at that offset only, so the row offset of a row past SR does no harm
             int soff = (ih0 + pw) * rowB;
 #pragma unroll
-            for (int j = 0; j < RROWS; ++j, soff += 4 * rowB) {
-                if (4 * j + 3 < G::SR || pw + 4 * j < G::SR) {   // (the rows past SR exist in LDS only)
+            for (int j = 0; j < RROWS; ++j, soff += 4 * rowB)
 #pragma unroll
-                    for (int q = 0; q < G::PASSES; ++q)
-                        v[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], soff, 0));
-                }
-            }
+                for (int q = 0; q < G::PASSES; ++q)
+                    v[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, j == RROWS - 1 ? vlast[q] : voff[q], soff, 0));
             return;
         }
 #pragma unroll
@@ -106,7 +107,7 @@ struct StripStager {
             const bool in = pw + 4 * j < G::SR && ih >= 0 && ih < IH;   // uniform
 #pragma unroll
             for (int q = 0; q < G::PASSES; ++q)
-                v[j][q] = in ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[q], ih * rowB, 0)) : 0.f;
+                v[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, in ? voff[q] : kBeyond, in ? ih * rowB : 0, 0));
         }
     }
     // strip: start of the strip buffer to fill.  Whole passes and all RROWS rows are written: what lies
