@@ -70,7 +70,8 @@ struct StripStager {
     static constexpr int kBeyond = (int)0x80000000u;
     float v[RROWS][G::PASSES];
     int voff[G::PASSES], vlast[G::PASSES];   // byte offsets of this lane's floats in an image row; the same for the wave's last row
-    int band = -1;
+    int band = -1, img = -1;
+    __amdgpu_buffer_rsrc_t rs;   // image img of X
 
     // tile = (image n, band c of 16 output columns, row tile t of 4 output rows); all wave-uniform
     __device__ __forceinline__ void fetch(const float *X, int n, int c, int t, int pw, int lane, int IH, int IW, int p)
@@ -86,8 +87,10 @@ struct StripStager {
                 vlast[q] = pw + 4 * (RROWS - 1) < G::SR ? voff[q] : kBeyond;   // (the rows past SR exist in LDS only)
             }
         }
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(X) + (long)n * IH * rowFloats, 0, IH * rowFloats * 4, 0x00020000);
+        if (n != img) {   // uniform: one descriptor per image
+            img = n;
+            rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(X) + (long)n * IH * rowFloats, 0, IH * rowFloats * 4, 0x00020000);
+        }
         const int ih0 = 4 * t * G::S_ - p, rowB = rowFloats * 4;
         static_assert(4 * (RROWS - 1) < G::SR, "only a wave's last row can lie past the strip");
         if (ih0 >= 0 && ih0 + G::SR <= IH) {

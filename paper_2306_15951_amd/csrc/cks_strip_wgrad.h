@@ -94,12 +94,18 @@ __global__ void __launch_bounds__(kStripThreads) strip_wgrad(const StripWgradPar
         constexpr int kBeyond = (int)0x80000000u;
         const int imgY = P.OH * P.OW * P.OC;     // floats of dY per image (the host checks: below 2 GiB)
         int a_band = -1, a_voff[VEC ? 1 : 4];    // byte offsets of this thread's floats in a tile row, or kBeyond
+        int a_img = -1;
+        __amdgpu_buffer_rsrc_t rs;               // image a_img of dY
         auto fetch = [&]() {
             if (ftile >= tile_end) return;   // uniform
             // (made scalar explicitly: the cursor is uniform, but lives across divergent code)
             const int n = __builtin_amdgcn_readfirstlane(fn), c = __builtin_amdgcn_readfirstlane(fc), t = __builtin_amdgcn_readfirstlane(ft);
             ++ftile;
             if (++ft == P.nRowTiles) { ft = 0; if (++fc == P.nBands) { fc = 0; ++fn; } }
+            if (n != a_img) {   // uniform, and before the lanes part ways: the descriptor stays in scalar registers
+                a_img = n;
+                rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + (long)n * imgY), 0, imgY * 4, 0x00020000);
+            }
             stager.fetch(P.X, n, c, t, pw, lane, P.IH, P.IW, P.p);
             if (!a_lane) return;
             const int ow0 = c * 16;
@@ -109,8 +115,6 @@ __global__ void __launch_bounds__(kStripThreads) strip_wgrad(const StripWgradPar
 #pragma unroll
                 for (int i = 0; i < (VEC ? 1 : 4); ++i) a_voff[i] = 16 * ptid + 4 * i < a_bytes ? 16 * ptid + 4 * i : kBeyond;
             }
-            const __amdgpu_buffer_rsrc_t rs =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.dY + (long)n * imgY), 0, imgY * 4, 0x00020000);
             int soff = ((4 * t) * P.OW + ow0) * P.OC * 4;
             const int rowB = P.OW * P.OC * 4;
             if (VEC && 4 * t + 4 <= P.OH) {   // uniform
