@@ -538,7 +538,8 @@ int conv_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_
     if (!X || !Wt || !Y) return CKS_ERR_NULL;
     const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
     // image stems: input strip in LDS, addressing known at compile time
-    if ((long long)H * W * C * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
+    // (an image of X and one of Y are each addressed with 31 bits of bytes)
+    if ((long long)H * W * C * 4 < (1LL << 31) && (long long)g.OH * g.OW * OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
         switch (strip_geometry(g)) {
             case 1: return launch_strip_fwd<7, 7, 3, 2>(g, X, Wt, Y, st);
             case 2: return launch_strip_fwd<3, 3, 3, 1>(g, X, Wt, Y, st);

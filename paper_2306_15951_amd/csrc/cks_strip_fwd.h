@@ -243,11 +243,14 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
     const float *a_last = h ? Ss + (STRIP - 1) - kLastImm : Ss + rowoff;
     const float *b_ptr = Ws + (wn * 32 + (lane & 31)) * LDW + h;
 
-    // Y: pixel (th, tw) of the tile is row oh0+th, column ow0+tw; each tile row is a descriptor
+    // Y: pixel (th, tw) of the tile is row oh0+th, column ow0+tw.  One descriptor per image, the tile row a
+    // scalar offset; a lane whose channel or tile column does not exist carries an offset beyond the image
+    // (set when the band changes: only a row's last band can be narrower than 16 columns).
     const int col = oc0 + wn * 32 + (lane & 31);
     int yoff[8];   // register r -> tile column 8*((r/4)%2) + 4h + r%4; tile row 2*wm + r/8
-#pragma unroll
-    for (int e = 0; e < 8; ++e) yoff[e] = col < P.OC ? ((8 * (e >> 2) + 4 * h + (e & 3)) * P.OC + col) * 4 : kBeyond;
+    int yimg = -1, yband = -1;
+    __amdgpu_buffer_rsrc_t rsY;
+    const int imgY = P.OH * P.OW * P.OC;   // floats of Y per image (the host checks: below 2 GiB)
 
     __syncthreads();
     for (int tile = tile_beg; tile < tile_end; ++tile) {
@@ -261,15 +264,29 @@ __global__ void __launch_bounds__(kStripThreads) strip_fwd(const StripFwdParams 
         const int n = __builtin_amdgcn_readfirstlane(cn), c = __builtin_amdgcn_readfirstlane(cc),
                   tt = __builtin_amdgcn_readfirstlane(ct);
         advance();
-        const int ow0 = c * 16, cols = min(16, P.OW - ow0);
+        const int ow0 = c * 16;
+        if (n != yimg) {   // uniform
+            yimg = n;
+            rsY = __builtin_amdgcn_make_buffer_rsrc(P.Y + (long)n * imgY, 0, imgY * 4, 0x00020000);
+        }
+        if (c != yband) {   // uniform
+            yband = c;
+            const int cols = min(16, P.OW - ow0);
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int oh = 4 * tt + 2 * wm + half;
-            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-                P.Y + (((long)n * P.OH + min(oh, P.OH - 1)) * P.OW + ow0) * P.OC, 0, oh < P.OH ? cols * P.OC * 4 : 0, 0x00020000);
+            for (int e = 0; e < 8; ++e) {
+                const int twe = 8 * (e >> 2) + 4 * h + (e & 3);
+                yoff[e] = (col < P.OC && twe < cols) ? (twe * P.OC + col) * 4 : kBeyond;
+            }
+        }
+        const int oh0 = 4 * tt + 2 * wm, rowB = P.OW * P.OC * 4;
+        int soff = (oh0 * P.OW + ow0) * P.OC * 4;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[8 * half + e]), rs, yoff[e], 0, 0);
+        for (int half = 0; half < 2; ++half, soff += rowB) {
+            if (oh0 + half < P.OH) {   // uniform (the scalar offset takes no part in the range check)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[8 * half + e]), rsY, yoff[e], soff, 0);
+            }
         }
         __syncthreads();
     }
