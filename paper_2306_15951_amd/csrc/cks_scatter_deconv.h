@@ -17,11 +17,13 @@
 //      LDS scratch (the MFMA result layout has the addends in different lanes);
 //   2. across rows:    dX row (ih+p) = sum_{fh = (ih+p) mod s, +s, ...} Q[(ih+p-fh)/s][fh],
 //      by the staging waves when the sweep has passed the row, from a ring of Q rows.
-// A workgroup owns one image and a band of 16 dY columns and sweeps it top to
-// bottom, four dY rows (one per MFMA wave) per step.  Neighbouring bands overlap
-// in (FW - s) dX pixel columns: a band writes its share of the columns it has in
-// common with its left neighbour to a small side buffer, and add_heads adds
-// that to dX afterwards, so no two workgroups ever add to one address.
+// A band of 16 dY columns of one image is swept top to bottom, four dY rows (one
+// per MFMA wave) per step; the steps of all bands, in order, are dealt to the
+// workgroups in equal consecutive runs.  Neighbouring bands overlap in (FW - s) dX
+// pixel columns, and a run that starts inside a band shares (FH - s) dX rows with
+// the run above it: a workgroup writes its share of such columns and rows to small
+// side buffers, and add_heads adds them to dX afterwards, so no two workgroups
+// ever add to one address.
 //
 // Every global access is a buffer access "lane constant + scalar" against a
 // per-row descriptor: rows and pixels outside the tensors fall outside the
