@@ -363,12 +363,13 @@ WgradPlan plan_wgrad(const Geo &g)
     w.nTiles = (g.C + w.bn - 1) / w.bn;
     const long long tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
     const long long K = (long long)g.N * g.OH * g.OW;
-    // About four workgroups per compute unit, segments of at least 256 pixels,
-    // and -- since workgroups are dealt to the 8 dies in contiguous ranges of
-    // segments -- a multiple of 8 segments, so that every die works on whole
-    // segments (measured: 8 segments beat 7 or 9 by 10-15 %).
+    // Just under four workgroups per compute unit (measured: 1008 workgroups beat 1152 by 2-4 points,
+    // a fifth workgroup on half of the compute units costs more than the others' idle eighth), an
+    // even number of segments (odd counts lose 5 points: the workgroups are dealt to the 8 dies in
+    // contiguous ranges of segments), segments of at least 256 pixels; never fewer than 8 segments
+    // while that leaves at most 16 workgroups per compute unit (8 segments beat 7 or 9 by 10-15 %).
     long long gz = 4LL * kCUs / tiles;
-    if (gz >= kXcds) gz = (gz + kXcds - 2) / kXcds * kXcds;   // 10 -> 16: rather more segments than fewer
+    if (gz >= kXcds) gz &= ~1LL;
     else if (tiles * kXcds <= 16LL * kCUs) gz = kXcds;
     if (tiles * kXcds > 16LL * kCUs) {
         // Many tiles (> 2 per compute unit): still up to four segments of at least 1024 pixels.  The
