@@ -300,6 +300,30 @@ constexpr int kWgradVariants[][6] = {
 
 // G_Z (Section IV.C: the number of segments trades parallelism against the
 // memory for partial sums) is derived from the compute-unit count, see below.
+// Segments (G_Z of Section IV.C's map-reduce) for `tiles` output tiles over K pixels.
+long long wgrad_segments(long long tiles, long long K)
+{
+    // Just under four workgroups per compute unit (measured: 1008 workgroups beat 1152 by 2-4 points,
+    // a fifth workgroup on half of the compute units costs more than the others' idle eighth), an
+    // even number of segments (odd counts lose 5 points: the workgroups are dealt to the 8 dies in
+    // contiguous ranges of segments), segments of at least 256 pixels; never fewer than 8 segments
+    // while that leaves at most 16 workgroups per compute unit (8 segments beat 7 or 9 by 10-15 %).
+    long long gz = 4LL * kCUs / tiles;
+    if (gz >= kXcds) gz &= ~1LL;
+    else if (tiles * kXcds <= 16LL * kCUs) gz = kXcds;
+    if (tiles * kXcds > 16LL * kCUs) {
+        // Many tiles (> 2 per compute unit): still up to four segments of at least 1024 pixels (eight
+        // up to 1024 tiles).  The finer grain evens out the compute units' shares and keeps a segment's
+        // X / dY rows in L2 while all its tiles use them (measured on 512-channel 5x5 layers: 4
+        // segments 74-85 % of peak, one segment 57-69 %; on 576 tiles with 12544 pixels: 8 segments
+        // 88.8 %, 4 segments 85.7 %).
+        const long long most = tiles <= 1024 ? 8 : 4;
+        gz = K / 1024 < most ? K / 1024 : most;
+    }
+    while (gz > 1 && K / gz < 256) gz = gz > kXcds ? gz - kXcds : gz / 2;
+    return gz < 1 ? 1 : gz;
+}
+
 WgradPlan plan_wgrad(const Geo &g)
 {
     WgradPlan w;
@@ -349,7 +373,15 @@ WgradPlan plan_wgrad(const Geo &g)
     // and a long contraction axis (measured: 128x128 tiles lose 5-8 points on every layer, 128x64
     // gain 3 on 576 tiles with 12544 pixels, lose 4 on 576 tiles with 4096 pixels or on 1600 tiles)
     const long long tiles64 = (long long)g.FH * g.FW * ((g.OC + 63) / 64) * ((g.C + 63) / 64);
-    w.variant = (g.OC >= 96 && tiles64 > 128 && tiles64 <= 1024 && (long long)g.N * g.OH * g.OW >= 8192) ? 5 : 4;
+    // The 64x64 tile also exists with its chunks loaded straight into LDS (whole chunks of 32 images, 16-byte
+    // vectors), which is worth more than the wider tile (576 tiles, 12544 pixels: 88.8 against 87.5 %; 400
+    // tiles: +5 points) -- unless its workgroups would come to between 4 and 8 per compute unit, where the
+    // uneven shares cost more (144 tiles: 1152 workgroups 69 %, the wider tile's 1008 workgroups 79 %).
+    const long long K = (long long)g.N * g.OH * g.OW;
+    const bool lds_direct = g.N % 32 == 0 && g.C % 4 == 0 && g.OC % 4 == 0;
+    const long long wgs64 = tiles64 * wgrad_segments(tiles64, K);
+    const bool prefer64 = lds_direct && (wgs64 <= 4LL * kCUs || wgs64 >= 8LL * kCUs);
+    w.variant = (!prefer64 && g.OC >= 96 && tiles64 > 128 && tiles64 <= 1024 && K >= 8192) ? 5 : 4;
     long long gz_override = 0;
     if (const char *t = tune) {
         int v = -1, z = 0;
@@ -362,24 +394,7 @@ WgradPlan plan_wgrad(const Geo &g)
     w.mTiles = (g.OC + w.bm - 1) / w.bm;
     w.nTiles = (g.C + w.bn - 1) / w.bn;
     const long long tiles = (long long)g.FH * g.FW * w.mTiles * w.nTiles;
-    const long long K = (long long)g.N * g.OH * g.OW;
-    // Just under four workgroups per compute unit (measured: 1008 workgroups beat 1152 by 2-4 points,
-    // a fifth workgroup on half of the compute units costs more than the others' idle eighth), an
-    // even number of segments (odd counts lose 5 points: the workgroups are dealt to the 8 dies in
-    // contiguous ranges of segments), segments of at least 256 pixels; never fewer than 8 segments
-    // while that leaves at most 16 workgroups per compute unit (8 segments beat 7 or 9 by 10-15 %).
-    long long gz = 4LL * kCUs / tiles;
-    if (gz >= kXcds) gz &= ~1LL;
-    else if (tiles * kXcds <= 16LL * kCUs) gz = kXcds;
-    if (tiles * kXcds > 16LL * kCUs) {
-        // Many tiles (> 2 per compute unit): still up to four segments of at least 1024 pixels.  The
-        // finer grain evens out the compute units' shares and keeps a segment's X / dY rows in L2
-        // while all its tiles use them (measured on 512-channel 5x5 layers: 4 segments 74-85 % of
-        // peak, one segment 57-69 %).
-        gz = K / 1024 < 4 ? K / 1024 : 4;
-    }
-    while (gz > 1 && K / gz < 256) gz = gz > kXcds ? gz - kXcds : gz / 2;
-    if (gz < 1) gz = 1;
+    long long gz = wgrad_segments(tiles, K);
     if (gz_override > 0) gz = gz_override;
     if (gz < 1) gz = 1;
     if (gz > 512) gz = 512;
