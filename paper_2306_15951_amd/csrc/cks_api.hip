@@ -105,16 +105,27 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     P.nTiles = (cols + BN - 1) / BN;
     const long long items = (long long)P.itemsH * P.itemsW;
     const long long total = items * P.mTiles * P.nTiles;
-    // bands: at least four per die if there are enough items, at most one row of items each
+    // Bands: at least four per die if there are enough items, at most one row of items each.  With few
+    // items (under 16 per die) that deals the dies unequal shares -- 49 positions of 32 tiles dealt position
+    // by position kept one die busy 25 % longer than the mean -- so bands are then two workgroups: every die
+    // gets the same mix of positions whatever their number (79 -> 86 % on that layer; what the dies' caches
+    // lose in locality did not show).  Not for KS-deconv with several classes: its class-major list wants
+    // neighbouring positions on one die (bands of 16 or 64 workgroups instead of 32 cost 12 points on the
+    // stride-2 benchmark layer).
+    P.pairFlip = OP == OP_FWD || (P.sh == 1 && P.sw == 1);
     long long g = items / (4 * kXcds);
     g = g < 1 ? 1 : (g > P.itemsW ? P.itemsW : g);
-    const long long bandBlocks = g * P.mTiles * P.nTiles;
-    const long long bands = (total + bandBlocks - 1) / bandBlocks;
+    long long bandBlocks = P.pairFlip && items < 16 * kXcds ? 2 : g * P.mTiles * P.nTiles;
+    if (const char *t = getenv("CKS_TUNE_BAND")) { if (atoi(t) > 0) bandBlocks = atoi(t); }   // tuning experiments only
+    // whole rounds of 8 bands go to the dies band by band, the rest in 8 equal pieces (banded_work)
+    const long long rounds = total / (bandBlocks * kXcds);
+    const long long covered = rounds * kXcds * bandBlocks, remPerDie = (total - covered + kXcds - 1) / kXcds;
     // (whole groups of 32 workgroups per die: banded_work permutes within them; the surplus workgroups exit at once)
-    const long long perDie = ((bands + kXcds - 1) / kXcds * bandBlocks + 31) / 32 * 32;
+    const long long perDie = (rounds * bandBlocks + remPerDie + 31) / 32 * 32;
     const long long blocks = perDie * kXcds;
     if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
     P.total = (int)total;
+    P.fullSlots = (int)(rounds * bandBlocks); P.remPerDie = (int)remPerDie; P.covered = (int)covered;
     P.bandBlocks = (int)bandBlocks;
     P.dBand = make_fastdiv(P.bandBlocks);
     P.dNT = make_fastdiv(P.nTiles);
@@ -124,7 +135,6 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     P.dSw = make_fastdiv(P.sw);
     P.pmodsH = P.ph % P.sh;
     P.pmodsW = P.pw % P.sw;
-    P.pairFlip = OP == OP_FWD || (P.sh == 1 && P.sw == 1);
     {
         // output rows of a tile are one image apart
         const long long rowO = OP == OP_FWD ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;

@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
     float *As = smem;                      // [2][BM][32]
     float *Bs = smem + 2 * BM * KC;        // [2][BN][32], or [2][32][BN] (K-major)
 
-    const int work = banded_work(blockIdx.x, P.dBand, P.pairFlip);
+    const int work = banded_work(blockIdx.x, P);
     if (work >= P.total) return;
     const int wq = fdiv(work, P.dNT), nt = work - wq * P.nTiles;
     const int item = fdiv(wq, P.dMT), mt = wq - item * P.mTiles;

@@ -54,6 +54,7 @@ struct RowRunParams {
     int pmodsH, pmodsW;   // ph mod sh, pw mod sw
     int bufStore;         // the tile's BM output rows span less than 2 GiB: stores go through a buffer descriptor
     int pairFlip;         // see banded_work
+    int fullSlots, remPerDie, covered;   // see banded_work
 };
 
 struct RunSet {
@@ -143,20 +144,28 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 // bandBlocks consecutive workgroups (tiles of neighbouring items, which share
 // operands and so that die's L2); bands go to the dies in a serpentine order,
 // so every die gets the same mix of expensive interior and cheap border items.
+// That covers the whole rounds of 8 bands (slots below fullSlots of every die, workgroups below
+// `covered`); what is left -- less than a round -- is cut into 8 equal contiguous pieces of remPerDie
+// workgroups, one per die: a 49th band as a whole would keep one die busy a seventh longer than the others.
 // Within a die the hardware deals consecutive workgroups to its 32 compute units round-robin (observed:
 // workgroups j and j + 32 of a die share a compute unit), and items are listed expensive first: with `flip`
 // every second group of 32 is walked backwards, so that the workgroups resident together on a compute unit
 // are an expensive and a cheap one rather than two of a kind.  (Not for KS-deconv with several classes: its
 // list is class-major, workgroups 32 apart are neighbouring positions of different classes that read the
 // same dY rows, and sharing a compute unit's cache is worth more there: -12 points on cfg2 when flipped.)
-__device__ inline int banded_work(int bid, const FastDiv &dBand, int flip)
+// A slot without work returns P.total.
+__device__ inline int banded_work(int bid, const RowRunParams &P)
 {
     const int xcd = bid % kXcds;
     int slot = bid / kXcds;
-    if (flip && (slot & 32)) slot ^= 31;
-    const int round = fdiv(slot, dBand);
-    const int band = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
-    return band * dBand.d + (slot - round * dBand.d);
+    if (P.pairFlip && (slot & 32)) slot ^= 31;
+    if (slot < P.fullSlots) {
+        const int round = fdiv(slot, P.dBand);
+        const int band = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
+        return band * P.dBand.d + (slot - round * P.dBand.d);
+    }
+    const int j = slot - P.fullSlots;
+    return j < P.remPerDie ? P.covered + xcd * P.remPerDie + j : P.total;
 }
 
 // Store of a workgroup's tile (shared by the kernels of this file and of cks_rowrun_dma.h).  Every output
@@ -234,7 +243,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     float *As = smem;                 // [2][BM][LDK]
     float *Bs = smem + 2 * BM * LDK;  // [2][BN][LDK]
 
-    const int work = banded_work(blockIdx.x, P.dBand, P.pairFlip);
+    const int work = banded_work(blockIdx.x, P);
     if (work >= P.total) return;
     const int wq = fdiv(work, P.dNT), nt = work - wq * P.nTiles;
     const int item = fdiv(wq, P.dMT), mt = wq - item * P.mTiles;
