@@ -279,8 +279,9 @@ __global__ void __launch_bounds__(kThreads) patch_gemm_fast(const PatchGemmParam
 
     const int NC = P.N / KC;                  // chunks per output position
     const int Ct = P.OH * P.OW * NC;
-    const int seg = (Ct + P.GZ - 1) / P.GZ;
-    const int cbeg = min(z * seg, Ct), T = min(cbeg + seg, Ct) - cbeg;
+    // segment z of G_Z: the chunks are dealt evenly, the first Ct mod G_Z segments get one more
+    const int seg = Ct / P.GZ, extra = Ct - seg * P.GZ;
+    const int cbeg = z * seg + min(z, extra), T = seg + (z < extra ? 1 : 0);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wk = wave % WAVES_K, wn = (wave / WAVES_K) % WAVES_N, wm = wave / (WAVES_K * WAVES_N);

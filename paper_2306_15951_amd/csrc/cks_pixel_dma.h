@@ -87,8 +87,9 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_dma(const PixelGemmParams
     const int nOH = max(oh_e - oh_s, 0), nOW = max(ow_e - ow_s, 0);
     const int NC = P.dNC.d;                        // chunks per (oh,ow): N / 32
     const int Ct = nOH * nOW * NC;                 // chunks of this tap
-    const int seg = fdiv(Ct + P.GZ - 1, P.dGZ);
-    const int cbeg = min(z * seg, Ct), T = min(cbeg + seg, Ct) - cbeg;
+    // segment z of G_Z: the chunks are dealt evenly, the first Ct mod G_Z segments get one more
+    const int seg = fdiv(Ct, P.dGZ), extra = Ct - seg * P.GZ;
+    const int cbeg = z * seg + min(z, extra), T = seg + (z < extra ? 1 : 0);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
