@@ -172,6 +172,10 @@ MID = [
     ("lds_direct_ragged_columns", 33, 68, 7, 7, 64, 3, 3, 1, 1),
     ("lds_direct_s3_5x4", 32, 32, 13, 11, 128, 5, 4, 3, 2),
     ("lds_direct_narrow_output", 130, 32, 9, 9, 40, 3, 3, 1, 1),
+    # many positions and a last, partial round of bands that is dealt to the dies in pieces (row-major
+    # list with bands of a row; class-major list of the stride-2 input gradient)
+    ("lds_direct_partial_round", 64, 64, 12, 13, 64, 3, 3, 1, 1),
+    ("lds_direct_partial_round_s2", 64, 64, 25, 23, 64, 3, 3, 2, 1),
     # more bands than compute units: the input gradient's workgroups take runs of sweep steps that
     # start and end inside bands, and the rows two runs share are added afterwards
     ("stem_row_heads", 37, 3, 24, 224, 64, 7, 7, 2, 3),
