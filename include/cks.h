@@ -86,10 +86,12 @@ int cks_conv2d_fwd(const float *X, const float *Wt, float *Y,
  * written to the workspace by cks_kernel_split and consumed by
  * cks_deconv2d_presplit.  Layers with C < 8 and OC <= 64 run Stage 2&3
  * tap-stationary and compose the result in on-chip memory; they use the
- * workspace for the rows and columns neighbouring workgroups share.  The
- * workspace must always have cks_deconv2d_workspace bytes; the result does not
- * depend on which variant runs beyond rounding, and every variant is
- * reproducible bit for bit.
+ * workspace for the rows and columns neighbouring workgroups share.
+ * cks_deconv2d_workspace is what the call needs whatever the alignment of its
+ * pointers; a call whose sub-kernels are read from Wt in place uses no
+ * workspace and accepts ws = NULL, any other call returns CKS_ERR_WORKSPACE
+ * without it.  The result does not depend on which variant runs beyond
+ * rounding, and every variant is reproducible bit for bit.
  * dY [N,OH,OW,OC] in, Wt [OC,FH,FW,C] in, dX [N,H,W,C] out. */
 int cks_deconv2d(const float *dY, const float *Wt, float *dX,
                  int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
@@ -141,23 +143,36 @@ int cks_dilated_conv2d_wgrad_hw(const float *X, const float *dY, float *dW,
                                 int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                                 void *ws, size_t ws_bytes, void *stream);
 
-/* ---- the stages on their own (what the three calls above are made of) ---- */
+/* ---- the stages on their own (what the three calls above are made of) ----
+ *
+ * Section V.A measures the operators also with "the filter operations done
+ * before the loop": cks_kernel_split once, cks_deconv2d_presplit per step.
+ * Each stage exists with one stride / padding and, suffixed _hw, with
+ * <sh sw>, <ph pw> per axis (Table I), the former calling the latter. */
 
 /* Stage 1 of KS-deconv (Section IV.B, Algorithm 2 Stage 1): rotate the filter
- * by 180 degrees and split it into stride*stride sub-kernels.  Sub-kernel (y,x)
- * holds the taps fh = y + (oph-ch)*stride, fw = x + (opw-cw)*stride with
- * oph = ceil((FH-y)/stride) - 1, opw likewise.  The result is the paper's
- * zero-padded 6-D tensor with the two channel axes exchanged, so that the
- * contraction index (ch,cw,oc) of Stage 2 is contiguous:
- *   Cs[stride][stride][C][ceil(FH/stride)][ceil(FW/stride)][OC]
- * cks_kernel_split_bytes gives its size.  Every element of Cs is written. */
+ * by 180 degrees and split it into sh*sw sub-kernels.  Sub-kernel (y,x)
+ * holds the taps fh = y + (oph-ch)*sh, fw = x + (opw-cw)*sw with
+ * oph = ceil((FH-y)/sh) - 1, opw = ceil((FW-x)/sw) - 1.  The result is the
+ * paper's zero-padded 6-D tensor with the two channel axes exchanged, so that
+ * the contraction index (ch,cw,oc) of Stage 2 is contiguous:
+ *   Cs[sh][sw][C][ceil(FH/sh)][ceil(FW/sw)][OC]
+ * cks_kernel_split_bytes gives its size (0 on bad arguments).  Every element
+ * of Cs is written.  Wt [OC,FH,FW,C] in, Cs out, both in device memory. */
 size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride);
+size_t cks_kernel_split_bytes_hw(int C, int OC, int FH, int FW, int sh, int sw);
 int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream);
+int cks_kernel_split_hw(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int sh, int sw, void *stream);
 
-/* Stage 2&3 of KS-deconv-V2 (Algorithm 2B) on an already split filter. */
+/* Stage 2&3 of KS-deconv-V2 (Algorithm 2B) on an already split filter:
+ * dY [N,OH,OW,OC] in, Cs (as written by cks_kernel_split for the same
+ * strides) in, dX [N,H,W,C] out.  No workspace. */
 int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
                           int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
                           void *stream);
+int cks_deconv2d_presplit_hw(const float *dY, const float *Cs, float *dX,
+                             int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                             void *stream);
 
 /* Filter transposition of Section IV.A (last paragraph):
  * Wt[OC][FH][FW][C] -> Wout[FH][FW][C][OC]. */
@@ -166,6 +181,7 @@ int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, in
 /* Number of segments the contraction axis of cks_dilated_conv2d_wgrad is split
  * into for this geometry (the paper's G_Z); 0 on bad geometry. */
 int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
+int cks_dilated_conv2d_wgrad_segments_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw);
 
 /* The "map" half of Sk-dilated-V2 (Section IV.C): segment z of the contraction
  * axis writes its partial filter gradient to part[z], with
@@ -174,10 +190,40 @@ int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH
 int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *part,
                                       int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
                                       void *stream);
+int cks_dilated_conv2d_wgrad_partials_hw(const float *X, const float *dY, float *part,
+                                         int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                         void *stream);
 
 /* The "reduce" half: dW[e] = part[0][e] + part[1][e] + ... in that order,
  * for e < elems (= OC*FH*FW*C), segments >= 1. */
 int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream);
+
+/* ---- which kernels a call would enqueue (host only, no device is touched) ----
+ *
+ * Which kernel variant serves a call is a function of the geometry and of the
+ * alignment of the pointers (Section IV.E describes the paper's own library
+ * choosing between kernels in the same way).  cks_plan_hw runs the code path of
+ * the entry point named by `op` up to, but not including, the launches and
+ * writes one line per kernel to `text` (host memory, text_bytes long, always
+ * terminated):  name<template arguments> [workgroups x threads, lds bytes]
+ * Bit i of only_4byte_aligned marks the i-th pointer argument of that entry
+ * point (bit 3: the workspace) as 4-byte aligned only; others count as
+ * 16-byte aligned.  CKS_OP_REDUCE_PARTIALS is planned for elems = OC*FH*FW*C
+ * and the geometry's own number of segments.  Returns CKS_ERR_SHAPE on bad
+ * geometry, CKS_ERR_NULL without a buffer, CKS_ERR_WORKSPACE if the text did
+ * not fit, CKS_ERR_UNSUPPORTED for an unknown op. */
+typedef enum {
+    CKS_OP_CONV2D_FWD = 0,
+    CKS_OP_DECONV2D = 1,
+    CKS_OP_DILATED_CONV2D_WGRAD = 2,
+    CKS_OP_KERNEL_SPLIT = 3,
+    CKS_OP_DECONV2D_PRESPLIT = 4,
+    CKS_OP_FILTER_TRANSPOSE = 5,
+    CKS_OP_WGRAD_PARTIALS = 6,
+    CKS_OP_REDUCE_PARTIALS = 7
+} cks_op;
+int cks_plan_hw(int op, int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                unsigned only_4byte_aligned, char *text, size_t text_bytes);
 
 const char *cks_strerror(int status);
 int cks_last_hip_error(void);

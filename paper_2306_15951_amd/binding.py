@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libcks.so")
 _lib = None
 
 CKS_OK, CKS_ERR_NULL, CKS_ERR_SHAPE, CKS_ERR_WORKSPACE, CKS_ERR_HIP, CKS_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+(CKS_OP_CONV2D_FWD, CKS_OP_DECONV2D, CKS_OP_DILATED_CONV2D_WGRAD, CKS_OP_KERNEL_SPLIT, CKS_OP_DECONV2D_PRESPLIT,
+ CKS_OP_FILTER_TRANSPOSE, CKS_OP_WGRAD_PARTIALS, CKS_OP_REDUCE_PARTIALS) = range(8)
 
 _GEO = [ctypes.c_int] * 9
 _GEO_HW = [ctypes.c_int] * 11   # N, C, H, W, OC, FH, FW, sh, sw, ph, pw
@@ -43,6 +45,12 @@ _PROTOTYPES = {
     "cks_kernel_split": ([ctypes.c_void_p] * 2 + [ctypes.c_int] * 5 + [ctypes.c_void_p], ctypes.c_int),
     "cks_deconv2d_presplit": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p], ctypes.c_int),
     "cks_filter_transpose": ([ctypes.c_void_p] * 2 + [ctypes.c_int] * 4 + [ctypes.c_void_p], ctypes.c_int),
+    "cks_kernel_split_bytes_hw": ([ctypes.c_int] * 6, ctypes.c_size_t),
+    "cks_kernel_split_hw": ([ctypes.c_void_p] * 2 + [ctypes.c_int] * 6 + [ctypes.c_void_p], ctypes.c_int),
+    "cks_deconv2d_presplit_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_dilated_conv2d_wgrad_segments_hw": (_GEO_HW, ctypes.c_int),
+    "cks_dilated_conv2d_wgrad_partials_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_plan_hw": ([ctypes.c_int] + _GEO_HW + [ctypes.c_uint, ctypes.c_char_p, ctypes.c_size_t], ctypes.c_int),
     "cks_strerror": ([ctypes.c_int], ctypes.c_char_p),
     "cks_last_hip_error": ([], ctypes.c_int),
 }
@@ -271,3 +279,55 @@ def cks_dilated_conv2d_wgrad_hw(X, dY, dW, stride, padding, ws):
                                              N, C, H, W, OC, FH, FW, *stride, *padding, wp, wb, _stream()),
            "cks_dilated_conv2d_wgrad_hw")
     return dW
+
+
+def cks_kernel_split_bytes_hw(C, OC, FH, FW, stride):
+    return lib().cks_kernel_split_bytes_hw(C, OC, FH, FW, *stride)
+
+
+def cks_kernel_split_hw(Wt, Cs, stride):
+    """Cs[sh,sw,C,ceil(FH/sh),ceil(FW/sw),OC] <- Stage 1 of KS-deconv on Wt[OC,FH,FW,C]."""
+    OC, FH, FW, C = Wt.shape
+    sh, sw = stride
+    _check(lib().cks_kernel_split_hw(_ptr(Wt, "Wt"), _ptr(Cs, "Cs", (sh, sw, C, -(-FH // sh), -(-FW // sw), OC)),
+                                     C, OC, FH, FW, sh, sw, _stream()), "cks_kernel_split_hw")
+    return Cs
+
+
+def cks_deconv2d_presplit_hw(dY, Cs, dX, FH, FW, stride, padding):
+    N, H, W, C = dX.shape
+    OC = dY.shape[3]
+    sh, sw = stride
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    _check(lib().cks_deconv2d_presplit_hw(_ptr(dY, "dY", (N, OH, OW, OC)),
+                                          _ptr(Cs, "Cs", (sh, sw, C, -(-FH // sh), -(-FW // sw), OC)), _ptr(dX, "dX"),
+                                          N, C, H, W, OC, FH, FW, *stride, *padding, _stream()), "cks_deconv2d_presplit_hw")
+    return dX
+
+
+def cks_dilated_conv2d_wgrad_segments_hw(N, C, H, W, OC, FH, FW, stride, padding):
+    return lib().cks_dilated_conv2d_wgrad_segments_hw(N, C, H, W, OC, FH, FW, *stride, *padding)
+
+
+def cks_dilated_conv2d_wgrad_partials_hw(X, dY, part, FH, FW, stride, padding):
+    N, H, W, C = X.shape
+    OC = dY.shape[3]
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    gz = cks_dilated_conv2d_wgrad_segments_hw(N, C, H, W, OC, FH, FW, stride, padding)
+    _check(lib().cks_dilated_conv2d_wgrad_partials_hw(_ptr(X, "X"), _ptr(dY, "dY", (N, OH, OW, OC)),
+                                                      _ptr(part, "part", (gz, OC, FH, FW, C)),
+                                                      N, C, H, W, OC, FH, FW, *stride, *padding, _stream()),
+           "cks_dilated_conv2d_wgrad_partials_hw")
+    return part
+
+
+def cks_plan_hw(op, N, C, H, W, OC, FH, FW, stride, padding, only_4byte_aligned=0):
+    """The kernels entry point `op` (CKS_OP_*) would enqueue for this geometry and pointer alignment, as a
+    list of (kernel name with template arguments, launch shape) pairs.  Host only."""
+    buf = ctypes.create_string_buffer(4096)
+    _check(lib().cks_plan_hw(op, N, C, H, W, OC, FH, FW, *stride, *padding, only_4byte_aligned, buf, len(buf)), "cks_plan_hw")
+    out = []
+    for line in buf.value.decode().splitlines():
+        name, _, shape = line.partition(" [")
+        out.append((name, "[" + shape))
+    return out

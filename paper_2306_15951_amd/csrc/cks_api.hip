@@ -6,6 +6,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <mutex>
 #include <set>
 #include <utility>
@@ -27,7 +28,28 @@ using namespace cks;
 
 constexpr int kCUs = 256;  // compute units of one MI355X
 
+// Tuning experiments: a library built with -DCKS_TUNING reads CKS_TUNE_* environment variables that
+// force other tiles, segment counts and load paths for A/B measurements, and carries the kernel
+// instantiations only they can select.  The product build defines nothing of it: tune() is then a
+// constant and every branch that depends on it disappears.
+#ifdef CKS_TUNING
+constexpr bool kTuning = true;
+inline const char *tune(const char *name) { return getenv(name); }
+#else
+constexpr bool kTuning = false;
+constexpr const char *tune(const char *) { return nullptr; }
+#endif
+
 thread_local int g_last_hip_error = 0;
+
+// cks_plan_hw runs the very code path of an entry point with this recorder installed: launch() then
+// writes the kernel's name and launch shape into the text instead of enqueuing anything.
+struct PlanRecorder {
+    char *text;
+    size_t cap, len;
+    bool truncated;
+};
+thread_local PlanRecorder *g_plan = nullptr;
 
 struct Geo {
     int N, C, H, W, OC, FH, FW;
@@ -76,24 +98,74 @@ inline hipError_t allow_large_lds(const void *kernel)
     return e;
 }
 
-template <typename K, typename P>
-int launch(K kernel, const P &params, int blocks, size_t lds, hipStream_t st, int threads = kThreads)
+// A kernel's name as the demangler prints its instantiation, e.g. "rowrun_gemm_dma<2, 64, 64, 2, 2>":
+// base name, integer template arguments, then boolean ones.
+struct KName {
+    const char *base;
+    int nInts;
+    int ints[8];
+    int nBools;
+    bool bools[2];
+};
+inline KName kname(const char *base) { return KName{base, 0, {}, 0, {}}; }
+template <typename... I>
+inline KName kname(const char *base, I... ints)
+{
+    KName k{base, (int)sizeof...(I), {(int)ints...}, 0, {}};
+    return k;
+}
+inline KName with_bools(KName k, bool a) { k.nBools = 1; k.bools[0] = a; return k; }
+inline KName with_bools(KName k, bool a, bool b) { k.nBools = 2; k.bools[0] = a; k.bools[1] = b; return k; }
+
+void record_launch(const KName &k, long long blocks, int threads, size_t lds)
+{
+    PlanRecorder &R = *g_plan;
+    char one[192];
+    int n = snprintf(one, sizeof one, "%s", k.base);
+    if (k.nInts + k.nBools > 0) {
+        n += snprintf(one + n, sizeof one - n, "<");
+        for (int i = 0; i < k.nInts; ++i) n += snprintf(one + n, sizeof one - n, i ? ", %d" : "%d", k.ints[i]);
+        for (int i = 0; i < k.nBools; ++i)
+            n += snprintf(one + n, sizeof one - n, (i || k.nInts) ? ", %s" : "%s", k.bools[i] ? "true" : "false");
+        n += snprintf(one + n, sizeof one - n, ">");
+    }
+    n += snprintf(one + n, sizeof one - n, " [%lld x %d, lds %zu]\n", blocks, threads, lds);
+    if (R.text && R.len + (size_t)n + 1 <= R.cap) {
+        memcpy(R.text + R.len, one, (size_t)n + 1);
+        R.len += (size_t)n;
+    } else {
+        R.truncated = true;
+    }
+}
+
+template <typename K, typename... A>
+int launch_args(const KName &name, K kernel, int blocks, size_t lds, hipStream_t st, int threads, const A &...args)
 {
     if (lds > 160 * 1024) return CKS_ERR_SHAPE;
-    if (const char *t = getenv("CKS_TUNE_WG_PER_CU")) {   // tuning experiments only: cap the workgroups resident per compute unit
+    if (const char *t = tune("CKS_TUNE_WG_PER_CU")) {   // cap the workgroups resident per compute unit
         const int n = atoi(t);
         if (n > 0) {
             const size_t want = (size_t)(160 * 1024 / n) / 256 * 256;
             if (want > lds) lds = want;
         }
     }
+    if (g_plan) {
+        record_launch(name, blocks, threads, lds);
+        return CKS_OK;
+    }
     if (lds > 64 * 1024) {
         hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel));
         if (e != hipSuccess) return hip_fail(e);
     }
-    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), lds, st, params);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), lds, st, args...);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? CKS_OK : hip_fail(e);
+}
+
+template <typename K, typename P>
+int launch(const KName &name, K kernel, const P &params, int blocks, size_t lds, hipStream_t st, int threads = kThreads)
+{
+    return launch_args(name, kernel, blocks, lds, st, threads, params);
 }
 
 // ---------------------------------------------------------------- ConvV2 / KS-deconv Stage 2&3
@@ -116,7 +188,7 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     long long g = items / (4 * kXcds);
     g = g < 1 ? 1 : (g > P.itemsW ? P.itemsW : g);
     long long bandBlocks = P.pairFlip && items < 16 * kXcds ? 2 : g * P.mTiles * P.nTiles;
-    if (const char *t = getenv("CKS_TUNE_BAND")) { if (atoi(t) > 0) bandBlocks = atoi(t); }   // tuning experiments only
+    if (const char *t = tune("CKS_TUNE_BAND")) { if (atoi(t) > 0) bandBlocks = atoi(t); }   // tuning experiments only
     // whole rounds of 8 bands go to the dies band by band, the rest in 8 equal pieces (banded_work)
     const long long rounds = total / (bandBlocks * kXcds);
     const long long covered = rounds * kXcds * bandBlocks, remPerDie = (total - covered + kXcds - 1) / kXcds;
@@ -138,7 +210,7 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     {
         // output rows of a tile are one image apart
         const long long rowO = OP == OP_FWD ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;
-        P.bufStore = rowO * BM * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_BUFFER_STORES");
+        P.bufStore = rowO * BM * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_BUFFER_STORES");
     }
     const size_t lds = rowrun_lds_bytes<BM, BN>();
     // Fast loads need: 16-byte vectors, every run a whole number of 32-float
@@ -150,21 +222,26 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     // the default tiles also exist with their chunks loaded straight into LDS (same conditions as the fast loads)
     constexpr bool kHasDma = (BM == 64 && BN == 64 && WM == 2 && WN == 2) ||
                              (BM == 128 && BN == 32 && WM == 4 && WN == 1 && OP != OP_DECONV_W);   // (the in-place filter tile is laid out for 64 columns)
-    const bool dma = kHasDma && !getenv("CKS_TUNE_NO_LDS_DIRECT");
+    // (kernels that only a tuning build can select are not instantiated otherwise)
+    const bool dma = kHasDma && !tune("CKS_TUNE_NO_LDS_DIRECT");
+    constexpr bool kAlwaysDma = kHasDma && !kTuning;
     if constexpr (OP == OP_DECONV_W) {
         // the caller has checked deconv_in_place_ok: only the fast-load variants exist
         if constexpr (kHasDma)
-            if (dma) return launch(rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
-        return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
+            if (dma) return launch(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
+        if constexpr (!kAlwaysDma)
+            return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_FAST), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
     } else {
         const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (rowB * BN + rowB) * 4 < (1LL << 31) &&
-                          !getenv("CKS_TUNE_NO_FAST_LOADS");
+                          !tune("CKS_TUNE_NO_FAST_LOADS");
         if constexpr (kHasDma)
-            if (fast && dma) return launch(rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
-        if (fast) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
-        if (vec) return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
-        return launch(rowrun_gemm<OP, BM, BN, WM, WN, LOAD_SCALAR>, P, (int)blocks, lds, st);
+            if (fast && dma) return launch(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
+        if constexpr (!kAlwaysDma)
+            if (fast) return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_FAST), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
+        if (vec) return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_VEC), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
+        return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_SCALAR), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_SCALAR>, P, (int)blocks, lds, st);
     }
+    return CKS_ERR_UNSUPPORTED;   // not reached
 }
 
 // KS-deconv can take its sub-kernels straight from the OHWI filter (no Stage 1 launch, no
@@ -174,7 +251,7 @@ bool deconv_in_place_ok(const Geo &g, const float *dY, const float *Wt)
 {
     const long long rowA = (long long)g.OH * g.OW * g.OC, w = (long long)g.OC * g.FH * g.FW * g.C;
     return g.OC % 32 == 0 && g.C % 4 == 0 && aligned16(dY) && aligned16(Wt) && rowA * 129 * 4 < (1LL << 31) &&
-           w * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS") && !getenv("CKS_TUNE_SPLIT_DECONV");
+           w * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_FAST_LOADS") && !tune("CKS_TUNE_SPLIT_DECONV");
 }
 
 template <int OP>
@@ -189,10 +266,12 @@ int dispatch_rowrun(const RowRunParams &P, int rows, int cols, bool vec, hipStre
     int bn = cols >= 48 ? 64 : 32;
     if (bn == 32) bm = 128;
     (void)positions;
-    if (const char *t = getenv("CKS_TUNE_ROWRUN")) sscanf(t, "%d,%d", &bm, &bn);   // tuning experiments only
+#ifdef CKS_TUNING
+    if (const char *t = tune("CKS_TUNE_ROWRUN")) sscanf(t, "%d,%d", &bm, &bn);
     if (bm == 128 && bn == 128) return launch_rowrun<OP, 128, 128, 2, 2>(P, rows, cols, vec, st);
     if (bm == 128 && bn == 64) return launch_rowrun<OP, 128, 64, 2, 2>(P, rows, cols, vec, st);
     if (bm == 64 && bn == 128) return launch_rowrun<OP, 64, 128, 2, 2>(P, rows, cols, vec, st);
+#endif
     if (bm == 64 && bn == 64) return launch_rowrun<OP, 64, 64, 2, 2>(P, rows, cols, vec, st);
     return launch_rowrun<OP, 128, 32, 4, 1>(P, rows, cols, vec, st);
 }
@@ -236,7 +315,7 @@ int launch_pack(const float *Wt, float *Out, int C, int OC, int FH, int FW, int 
     const long long slots = MODE == PACK_SPLIT ? (long long)sh * sw * P.CHp * P.CWp : (long long)FH * FW;
     const long long blocks = slots * P.ocTiles * P.icTiles;
     if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
-    return launch(pack_filter<MODE>, P, (int)blocks, 0, st);
+    return launch(kname("pack_filter", MODE), pack_filter<MODE>, P, (int)blocks, 0, st);
 }
 
 // ---------------------------------------------------------------- Sk-dilated
@@ -270,11 +349,11 @@ int launch_strip_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hi
     if (!fits_i31(tiles * Q.nT)) return CKS_ERR_SHAPE;
     Q.tiles = (int)tiles;
     int per_cu = 2;   // workgroups per compute unit
-    if (const char *t = getenv("CKS_TUNE_STRIP_FWD")) per_cu = atoi(t) > 0 ? atoi(t) : 2;   // tuning experiments only
+    if (const char *t = tune("CKS_TUNE_STRIP_FWD")) per_cu = atoi(t) > 0 ? atoi(t) : 2;   // tuning experiments only
     const int groups = Q.tiles < per_cu * kCUs ? Q.tiles : per_cu * kCUs;
     Q.tilesPerBlock = (Q.tiles + groups - 1) / groups;
     const int blocks = ((Q.tiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
-    return launch(strip_fwd<FH, FW, IC, S>, Q, blocks, SG::lds_bytes(), st, kStripThreads);
+    return launch(kname("strip_fwd", FH, FW, IC, S), strip_fwd<FH, FW, IC, S>, Q, blocks, SG::lds_bytes(), st, kStripThreads);
 }
 
 template <int FH, int FW, int IC, int S>
@@ -288,8 +367,8 @@ int launch_strip_wgrad(const Geo &g, int GZ, const float *X, const float *dY, fl
     Q.tiles = g.N * Q.nBands * Q.nRowTiles;
     Q.tilesPerBlock = (Q.tiles + GZ - 1) / GZ;
     const size_t lds = strip_wgrad_lds_bytes<FH, FW, IC, S>();
-    if (veca) return launch(strip_wgrad<FH, FW, IC, S, true>, Q, GZ, lds, st, kStripThreads);
-    return launch(strip_wgrad<FH, FW, IC, S, false>, Q, GZ, lds, st, kStripThreads);
+    if (veca) return launch(with_bools(kname("strip_wgrad", FH, FW, IC, S), true), strip_wgrad<FH, FW, IC, S, true>, Q, GZ, lds, st, kStripThreads);
+    return launch(with_bools(kname("strip_wgrad", FH, FW, IC, S), false), strip_wgrad<FH, FW, IC, S, false>, Q, GZ, lds, st, kStripThreads);
 }
 
 struct WgradPlan {
@@ -338,7 +417,7 @@ WgradPlan plan_wgrad(const Geo &g)
 {
     WgradPlan w;
     w.patch = 0;
-    const char *tune = getenv("CKS_TUNE_WGRAD");   // "variant[,G_Z]": tuning experiments only
+    const char *tw = tune("CKS_TUNE_WGRAD");   // "variant[,G_Z]": tuning experiments only
     // Few input channels: a per-tap tile would be narrower than an MFMA block.
     // Put the whole filter patch (J = FH*FW*IC columns) into one tile if it
     // fits 5, 10 or 18 column blocks without wasting more than 30 % of them.
@@ -346,7 +425,7 @@ WgradPlan plan_wgrad(const Geo &g)
     // image stems: input strip in LDS (strip_wgrad), one segment per workgroup
     // (an image of X and one of dY, plus a tile's rows below it, are each addressed with 31 bits of bytes)
     if (strip_geometry(g) && g.OC <= 64 && (long long)g.H * g.W * g.C * 4 < (1LL << 31) &&
-        ((long long)g.OH + 4) * g.OW * g.OC * 4 < (1LL << 31) && !tune && !getenv("CKS_TUNE_NO_STRIP_WGRAD")) {
+        ((long long)g.OH + 4) * g.OW * g.OC * 4 < (1LL << 31) && !tw && !tune("CKS_TUNE_NO_STRIP_WGRAD")) {
         const long long tiles = (long long)g.N * ((g.OW + 15) / 16) * ((g.OH + 3) / 4);
         if (fits_i31(tiles)) {
             w.patch = 4;
@@ -359,7 +438,7 @@ WgradPlan plan_wgrad(const Geo &g)
             return w;
         }
     }
-    if (g.C < 48 && J <= 576 && !(tune && tune[0] == 't')) {
+    if (g.C < 48 && J <= 576 && !(tw && tw[0] == 't')) {
         const int nb = J <= 160 ? 5 : (J <= 320 ? 10 : 18);
         if (10 * J >= 7 * 32 * nb) {
             w.patch = nb == 5 ? 1 : (nb == 10 ? 2 : 3);
@@ -370,8 +449,8 @@ WgradPlan plan_wgrad(const Geo &g)
             // workgroups per compute unit that fit its LDS: one for the 18-block tile, else two
             long long gz = ((w.patch == 3 ? 1LL : 2LL) * kCUs + w.mTiles - 1) / w.mTiles;
             gz = gz < K / 256 ? gz : K / 256;
-            if (tune && tune[0] == 'p') {
-                const int z = atoi(tune + 1);
+            if (tw && tw[0] == 'p') {
+                const int z = atoi(tw + 1);
                 if (z > 0) gz = z;
             }
             if (gz < 1) gz = 1;
@@ -393,7 +472,7 @@ WgradPlan plan_wgrad(const Geo &g)
     const bool prefer64 = lds_direct && (wgs64 <= 4LL * kCUs || wgs64 >= 8LL * kCUs);
     w.variant = (!prefer64 && g.OC >= 96 && tiles64 > 128 && tiles64 <= 1024 && K >= 8192) ? 5 : 4;
     long long gz_override = 0;
-    if (const char *t = tune) {
+    if (const char *t = tw) {
         int v = -1, z = 0;
         if (t[0] == 't') ++t;
         if (sscanf(t, "%d,%d", &v, &z) >= 1 && v >= 0 && v < 7) w.variant = v;
@@ -425,25 +504,25 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
     P.dSw = make_fastdiv(P.sw);
     P.dGZ = make_fastdiv(P.GZ);
     P.dNC = make_fastdiv(P.N / KC > 0 ? P.N / KC : 1);
-    P.bufStore = P.sliceElems * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_BUFFER_STORES");
+    P.bufStore = P.sliceElems * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_BUFFER_STORES");
     // batch-inner ordering with scalar chunk offsets (see pixel_gemm_fast)
     // (its ceiling divisions shift their numerators by (FH + FW) strides: keep that within 31 bits)
     const long long smax = P.sh > P.sw ? P.sh : P.sw;
     const bool fast = veca && vecb && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
                       (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) &&
-                      (P.FH + P.FW + 2) * smax + P.IH + P.IW + P.FH + P.FW < (1LL << 30) && !getenv("CKS_TUNE_NO_FAST_LOADS");
+                      (P.FH + P.FW + 2) * smax + P.IH + P.IW + P.FH + P.FW < (1LL << 30) && !tune("CKS_TUNE_NO_FAST_LOADS");
     if constexpr (BM == 64 && BN == 64 && KC == 16 && WM == 2 && WN == 2 && WK == 1) {
         // the default tile also exists with its chunks (32 images) loaded straight into LDS
-        if (fast && P.N % kPixelDmaKC == 0 && !getenv("CKS_TUNE_NO_LDS_DIRECT")) {
+        if (fast && P.N % kPixelDmaKC == 0 && !tune("CKS_TUNE_NO_LDS_DIRECT")) {
             P.dNC = make_fastdiv(P.N / kPixelDmaKC);
-            return launch(pixel_gemm_dma, P, blocks, pixel_dma_lds_bytes(), st);
+            return launch(kname("pixel_gemm_dma"), pixel_gemm_dma, P, blocks, pixel_dma_lds_bytes(), st);
         }
     }
-    if (fast) return launch(pixel_gemm_fast<BM, BN, KC, WM, WN, WK>, P, blocks, lds, st);
-    if (veca && vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
-    if (veca) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
-    if (vecb) return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, true>, P, blocks, lds, st);
-    return launch(pixel_gemm<BM, BN, KC, WM, WN, WK, false, false>, P, blocks, lds, st);
+    if (fast) return launch(kname("pixel_gemm_fast", BM, BN, KC, WM, WN, WK), pixel_gemm_fast<BM, BN, KC, WM, WN, WK>, P, blocks, lds, st);
+    if (veca && vecb) return launch(with_bools(kname("pixel_gemm", BM, BN, KC, WM, WN, WK), true, true), pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
+    if (veca) return launch(with_bools(kname("pixel_gemm", BM, BN, KC, WM, WN, WK), true, false), pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
+    if (vecb) return launch(with_bools(kname("pixel_gemm", BM, BN, KC, WM, WN, WK), false, true), pixel_gemm<BM, BN, KC, WM, WN, WK, false, true>, P, blocks, lds, st);
+    return launch(with_bools(kname("pixel_gemm", BM, BN, KC, WM, WN, WK), false, false), pixel_gemm<BM, BN, KC, WM, WN, WK, false, false>, P, blocks, lds, st);
 }
 
 template <int WM, int WN, int WK, int NBW, int KC>
@@ -453,13 +532,13 @@ int launch_patch(PatchGemmParams P, bool veca, bool vecb, hipStream_t st)
     const int blocks = P.perXcd * kXcds;
     // batch-inner ordering with scalar chunk offsets (see patch_gemm_fast)
     const bool fast = veca && P.N % KC == 0 && (long long)P.N * P.IH * P.IW * P.IC * 4 < (1LL << 31) &&
-                      (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_FAST_LOADS");
+                      (long long)P.N * P.OH * P.OW * P.OC * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_FAST_LOADS");
     // (with 4-byte items, i.e. IC not a multiple of 4, the pixel order coalesces better: neighbouring patches overlap)
-    if (fast && vecb) return launch(patch_gemm_fast<WM, WN, WK, NBW, KC, true>, P, blocks, lds, st);
-    if (veca && vecb) return launch(patch_gemm<WM, WN, WK, NBW, KC, true, true>, P, blocks, lds, st);
-    if (veca) return launch(patch_gemm<WM, WN, WK, NBW, KC, true, false>, P, blocks, lds, st);
-    if (vecb) return launch(patch_gemm<WM, WN, WK, NBW, KC, false, true>, P, blocks, lds, st);
-    return launch(patch_gemm<WM, WN, WK, NBW, KC, false, false>, P, blocks, lds, st);
+    if (fast && vecb) return launch(with_bools(kname("patch_gemm_fast", WM, WN, WK, NBW, KC), true), patch_gemm_fast<WM, WN, WK, NBW, KC, true>, P, blocks, lds, st);
+    if (veca && vecb) return launch(with_bools(kname("patch_gemm", WM, WN, WK, NBW, KC), true, true), patch_gemm<WM, WN, WK, NBW, KC, true, true>, P, blocks, lds, st);
+    if (veca) return launch(with_bools(kname("patch_gemm", WM, WN, WK, NBW, KC), true, false), patch_gemm<WM, WN, WK, NBW, KC, true, false>, P, blocks, lds, st);
+    if (vecb) return launch(with_bools(kname("patch_gemm", WM, WN, WK, NBW, KC), false, true), patch_gemm<WM, WN, WK, NBW, KC, false, true>, P, blocks, lds, st);
+    return launch(with_bools(kname("patch_gemm", WM, WN, WK, NBW, KC), false, false), patch_gemm<WM, WN, WK, NBW, KC, false, false>, P, blocks, lds, st);
 }
 
 
@@ -565,7 +644,7 @@ int conv_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_
     const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
     // image stems: input strip in LDS, addressing known at compile time
     // (an image of X and one of Y are each addressed with 31 bits of bytes)
-    if ((long long)H * W * C * 4 < (1LL << 31) && (long long)g.OH * g.OW * OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_STRIP_FWD")) {
+    if ((long long)H * W * C * 4 < (1LL << 31) && (long long)g.OH * g.OW * OC * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_STRIP_FWD")) {
         switch (strip_geometry(g)) {
             case 1: return launch_strip_fwd<7, 7, 3, 2>(g, X, Wt, Y, st);
             case 2: return launch_strip_fwd<3, 3, 3, 1>(g, X, Wt, Y, st);
@@ -577,7 +656,7 @@ int conv_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_
     // whole filter patch as contraction axis and the filter resident in LDS.
     const int KP = (FH * FW * C + 15) / 16 * 16;
     if (C < 8 && KP <= kPatchFwdMaxKP && (long long)N * H * W * C * 4 < (1LL << 31) &&
-        (long long)N * g.OH * g.OW * OC * 4 < (1LL << 31) && !getenv("CKS_TUNE_NO_PATCH_FWD")) {
+        (long long)N * g.OH * g.OW * OC * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_PATCH_FWD")) {
         PatchFwdParams Q{};
         Q.X = X; Q.W = Wt; Q.Y = Y;
         Q.N = N; Q.IC = C; Q.IH = H; Q.IW = W; Q.OC = OC; Q.OH = g.OH; Q.OW = g.OW;
@@ -589,7 +668,7 @@ int conv_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_
         Q.tilesPerBlock = (Q.mTiles + groups - 1) / groups;
         const long long blocks = (long long)((Q.mTiles + Q.tilesPerBlock - 1) / Q.tilesPerBlock) * Q.nT;
         if (!fits_i31(blocks)) return CKS_ERR_SHAPE;
-        return launch(patch_fwd, Q, (int)blocks, patch_fwd_lds_bytes(KP), st, kPatchFwdThreads);
+        return launch(kname("patch_fwd"), patch_fwd, Q, (int)blocks, patch_fwd_lds_bytes(KP), st, kPatchFwdThreads);
     }
     const bool vec = (C % 4 == 0) && aligned16(X) && aligned16(Wt);
     return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), N, OC, vec, st);
@@ -616,9 +695,11 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
     const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
     if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, g.sh, g.sw) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!dY || !Wt || !dX) return CKS_ERR_NULL;
-    if (!ws || ws_bytes < deconv_workspace(g)) return CKS_ERR_WORKSPACE;
+    // (the variant that reads the filter in place uses no workspace: it may then be NULL)
+    const bool have_ws = ws && ws_bytes >= deconv_workspace(g);
     ScatterPlan S = plan_scatter(g);
-    if (S.ok && aligned16(dY) && aligned16(ws) && !getenv("CKS_TUNE_NO_SCATTER")) {
+    if (S.ok && !have_ws) return CKS_ERR_WORKSPACE;
+    if (S.ok && aligned16(dY) && aligned16(ws) && !tune("CKS_TUNE_NO_SCATTER")) {
         const int stride = g.sh, padding = g.ph;   // the same on both axes (plan_scatter)
         S.P.dY = dY; S.P.W = Wt; S.P.dX = dX; S.P.head = (float *)ws;
         S.P.rowhead = (float *)((char *)ws + S.headBytes);
@@ -626,9 +707,9 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
         if (stem) S.P.slots = kScatterStemSlots;
         const size_t lds = scatter_deconv_lds_bytes(S.NB, S.P.slots, FH);
         int rc;
-        if (S.NB == 4) rc = launch(scatter_deconv<4, false>, S.P, S.blocks, lds, st, kScatterThreads);
-        else if (stem) rc = launch(scatter_deconv<10, true>, S.P, S.blocks, lds, st, kScatterStemThreads);
-        else rc = launch(scatter_deconv<10, false>, S.P, S.blocks, lds, st, kScatterThreads);
+        if (S.NB == 4) rc = launch(with_bools(kname("scatter_deconv", 4), false), scatter_deconv<4, false>, S.P, S.blocks, lds, st, kScatterThreads);
+        else if (stem) rc = launch(with_bools(kname("scatter_deconv", 10), true), scatter_deconv<10, true>, S.P, S.blocks, lds, st, kScatterStemThreads);
+        else rc = launch(with_bools(kname("scatter_deconv", 10), false), scatter_deconv<10, false>, S.P, S.blocks, lds, st, kScatterThreads);
         if (rc != CKS_OK) return rc;
         const bool bandPart = S.P.nBands > 1 && S.P.OVF > 0;
         if (bandPart || S.rowheadBytes) {
@@ -647,12 +728,13 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
             const int per = kThreads / kScatterRP;
             const long long rowBlocks = S.rowheadBytes ? ((long long)S.blocks * S.P.HR + per - 1) / per : 0;
             if (!fits_i31(B.bandBlocks + rowBlocks)) return CKS_ERR_SHAPE;
-            rc = launch(add_heads, B, (int)(B.bandBlocks + rowBlocks), 0, st);
+            rc = launch(kname("add_heads"), add_heads, B, (int)(B.bandBlocks + rowBlocks), 0, st);
         }
         return rc;
     }
     if (deconv_in_place_ok(g, dY, Wt))
         return dispatch_rowrun<OP_DECONV_W>(rowrun_params<OP_DECONV_W>(g, dY, Wt, dX), N, C, true, st);
+    if (!have_ws) return CKS_ERR_WORKSPACE;
     int rc = kernel_split(Wt, (float *)ws, C, OC, FH, FW, g.sh, g.sw, st);
     if (rc != CKS_OK) return rc;
     return deconv_presplit(g, dY, (const float *)ws, dX, st);
@@ -700,13 +782,16 @@ int wgrad_partials(const Geo &g, const float *X, const float *dY, float *part, h
     P.perXcd = (P.total + kXcds - 1) / kXcds;
     P.sliceElems = (long)OC * FH * FW * C;
     switch (w.variant) {
+#ifdef CKS_TUNING
         case 0: return launch_pixel<128, 128, 16, 2, 2, 1>(P, veca, vecb, st);
         case 1: return launch_pixel<128, 64, 32, 2, 1, 2>(P, veca, vecb, st);
         case 2: return launch_pixel<64, 128, 32, 1, 2, 2>(P, veca, vecb, st);
         case 3: return launch_pixel<64, 64, 32, 1, 1, 4>(P, veca, vecb, st);
+        case 6: return launch_pixel<64, 128, 16, 2, 2, 1>(P, veca, vecb, st);
+#endif
         case 4: return launch_pixel<64, 64, 16, 2, 2, 1>(P, veca, vecb, st);
         case 5: return launch_pixel<128, 64, 16, 2, 2, 1>(P, veca, vecb, st);
-        default: return launch_pixel<64, 128, 16, 2, 2, 1>(P, veca, vecb, st);
+        default: return CKS_ERR_UNSUPPORTED;
     }
 }
 
@@ -847,15 +932,25 @@ int cks_dilated_conv2d_wgrad(const float *X, const float *dY, float *dW,
 
 // ---- stages
 
+size_t cks_kernel_split_bytes_hw(int C, int OC, int FH, int FW, int sh, int sw)
+{
+    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || sh < 1 || sw < 1) return 0;
+    return split_bytes(C, OC, FH, FW, sh, sw);
+}
+
 size_t cks_kernel_split_bytes(int C, int OC, int FH, int FW, int stride)
 {
-    if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || stride < 1) return 0;
-    return split_bytes(C, OC, FH, FW, stride, stride);
+    return cks_kernel_split_bytes_hw(C, OC, FH, FW, stride, stride);
+}
+
+int cks_kernel_split_hw(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int sh, int sw, void *stream)
+{
+    return kernel_split(Wt, Cs, C, OC, FH, FW, sh, sw, (hipStream_t)stream);
 }
 
 int cks_kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int stride, void *stream)
 {
-    return kernel_split(Wt, Cs, C, OC, FH, FW, stride, stride, (hipStream_t)stream);
+    return cks_kernel_split_hw(Wt, Cs, C, OC, FH, FW, stride, stride, stream);
 }
 
 int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, int FW, void *stream)
@@ -866,31 +961,50 @@ int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, in
     return launch_pack<PACK_TRANSPOSE>(Wt, Wout, C, OC, FH, FW, 1, 1, (hipStream_t)stream);
 }
 
-int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
-                          int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
-                          void *stream)
+int cks_deconv2d_presplit_hw(const float *dY, const float *Cs, float *dX,
+                             int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                             void *stream)
 {
     Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
     if (rc != CKS_OK) return rc;
     return deconv_presplit(g, dY, Cs, dX, (hipStream_t)stream);
 }
 
-int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+int cks_deconv2d_presplit(const float *dY, const float *Cs, float *dX,
+                          int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                          void *stream)
+{
+    return cks_deconv2d_presplit_hw(dY, Cs, dX, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, stream);
+}
+
+int cks_dilated_conv2d_wgrad_segments_hw(int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw)
 {
     Geo g;
-    if (check_geo(g, N, C, H, W, OC, FH, FW, stride, stride, padding, padding) != CKS_OK) return 0;
+    if (check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw) != CKS_OK) return 0;
     return plan_wgrad(g).GZ;
+}
+
+int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding)
+{
+    return cks_dilated_conv2d_wgrad_segments_hw(N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
+}
+
+int cks_dilated_conv2d_wgrad_partials_hw(const float *X, const float *dY, float *part,
+                                         int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                         void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return wgrad_partials(g, X, dY, part, (hipStream_t)stream);
 }
 
 int cks_dilated_conv2d_wgrad_partials(const float *X, const float *dY, float *part,
                                       int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
                                       void *stream)
 {
-    Geo g;
-    int rc = check_geo(g, N, C, H, W, OC, FH, FW, stride, stride, padding, padding);
-    if (rc != CKS_OK) return rc;
-    return wgrad_partials(g, X, dY, part, (hipStream_t)stream);
+    return cks_dilated_conv2d_wgrad_partials_hw(X, dY, part, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, stream);
 }
 
 int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream)
@@ -901,13 +1015,44 @@ int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segment
     const bool vec = elems % 4 == 0 && aligned16(part) && aligned16(dW);
     const int zl = segments >= 32 ? 16 : 1;                 // z-lanes per element
     const long per_block = (long)(kThreads / zl) * (vec ? 4 : 1);
-    const dim3 grid((unsigned)((elems + per_block - 1) / per_block)), block(kThreads);
-    if (zl == 16 && vec) hipLaunchKernelGGL((reduce_slices<16, 4>), grid, block, 0, st, part, dW, (long)elems, segments);
-    else if (zl == 16) hipLaunchKernelGGL((reduce_slices<16, 1>), grid, block, 0, st, part, dW, (long)elems, segments);
-    else if (vec) hipLaunchKernelGGL((reduce_slices<1, 4>), grid, block, 0, st, part, dW, (long)elems, segments);
-    else hipLaunchKernelGGL((reduce_slices<1, 1>), grid, block, 0, st, part, dW, (long)elems, segments);
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? CKS_OK : hip_fail(e);
+    const int blocks = (int)((elems + per_block - 1) / per_block);
+    const long n = (long)elems;
+    if (zl == 16 && vec) return launch_args(kname("reduce_slices", 16, 4), reduce_slices<16, 4>, blocks, 0, st, kThreads, part, dW, n, segments);
+    if (zl == 16) return launch_args(kname("reduce_slices", 16, 1), reduce_slices<16, 1>, blocks, 0, st, kThreads, part, dW, n, segments);
+    if (vec) return launch_args(kname("reduce_slices", 1, 4), reduce_slices<1, 4>, blocks, 0, st, kThreads, part, dW, n, segments);
+    return launch_args(kname("reduce_slices", 1, 1), reduce_slices<1, 1>, blocks, 0, st, kThreads, part, dW, n, segments);
+}
+
+// ---- which kernels a call would enqueue (host only)
+
+int cks_plan_hw(int op, int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                unsigned only_4byte_aligned, char *text, size_t text_bytes)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    if (!text || text_bytes == 0) return CKS_ERR_NULL;
+    // Stand-in addresses with the requested alignment; no entry point reads or writes through a
+    // pointer on the host, and with the recorder installed nothing reaches the device.
+    auto ptr = [&](int i) { return reinterpret_cast<float *>((uintptr_t)0x10000000u * (uintptr_t)(i + 1) + ((only_4byte_aligned >> i) & 1u) * 4u); };
+    float *a = ptr(0), *b = ptr(1), *c = ptr(2), *ws = ptr(3);
+    PlanRecorder R{text, text_bytes, 0, false};
+    text[0] = 0;
+    g_plan = &R;
+    switch (op) {
+        case CKS_OP_CONV2D_FWD: rc = conv_fwd(g, a, b, c, nullptr); break;
+        case CKS_OP_DECONV2D: rc = deconv(g, a, b, c, ws, deconv_workspace(g), nullptr); break;
+        case CKS_OP_DILATED_CONV2D_WGRAD: rc = wgrad(g, a, b, c, ws, wgrad_workspace(g), nullptr); break;
+        case CKS_OP_KERNEL_SPLIT: rc = kernel_split(a, b, C, OC, FH, FW, sh, sw, nullptr); break;
+        case CKS_OP_DECONV2D_PRESPLIT: rc = deconv_presplit(g, a, b, c, nullptr); break;
+        case CKS_OP_FILTER_TRANSPOSE: rc = cks_filter_transpose(a, b, C, OC, FH, FW, nullptr); break;
+        case CKS_OP_WGRAD_PARTIALS: rc = wgrad_partials(g, a, b, c, nullptr); break;
+        case CKS_OP_REDUCE_PARTIALS: rc = cks_reduce_partials(a, b, (int64_t)OC * FH * FW * C, plan_wgrad(g).GZ, nullptr); break;
+        default: rc = CKS_ERR_UNSUPPORTED; break;
+    }
+    g_plan = nullptr;
+    if (rc == CKS_OK && R.truncated) rc = CKS_ERR_WORKSPACE;
+    return rc;
 }
 
 const char *cks_strerror(int status)

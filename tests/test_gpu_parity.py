@@ -181,6 +181,27 @@ MID = [
     ("stem_row_heads", 37, 3, 24, 224, 64, 7, 7, 2, 3),
     ("rgb7_row_heads_oc16", 37, 3, 27, 230, 16, 7, 7, 2, 3),
     ("rgb3_row_heads", 40, 3, 12, 112, 8, 3, 3, 1, 1),
+    # the filter gradient's whole-patch tiles with 5, 10 and 18 column blocks in batch-innermost order
+    # (batch a multiple of the chunk, channel counts multiples of 4, 16-byte aligned tensors)
+    ("patch_fast_5_blocks", 64, 16, 9, 10, 64, 3, 3, 1, 1),
+    ("patch_fast_10_blocks_s2", 32, 32, 11, 9, 40, 3, 3, 2, 1),
+    ("patch_fast_18_blocks_4x4", 32, 32, 16, 15, 64, 4, 4, 1, 2),
+    # ... and in pixel order with channel counts that rule out 16-byte loads on either operand
+    ("patch_10_blocks_scalar_both", 10, 25, 9, 10, 7, 3, 3, 1, 1),
+    ("patch_10_blocks_scalar_dY", 10, 28, 9, 10, 7, 3, 3, 1, 1),
+    ("patch_10_blocks_scalar_X", 10, 25, 9, 10, 8, 3, 3, 1, 1),
+    ("patch_18_blocks_scalar_both", 9, 27, 8, 9, 7, 4, 4, 1, 2),
+    ("patch_18_blocks_scalar_dY", 9, 28, 8, 9, 7, 4, 4, 1, 2),
+    ("patch_18_blocks_scalar_X", 9, 27, 8, 9, 8, 4, 4, 2, 1),
+    # forward with 64 output columns per tile and an input channel count that rules out 16-byte loads
+    ("fwd_scalar_loads_wide", 20, 9, 7, 8, 50, 3, 3, 1, 1),
+    # input gradient through Stage 1 + Stage 2&3 on the split filter with whole 32-channel chunks of OC,
+    # loaded straight into LDS (C not a multiple of 4 rules out reading the filter in place)
+    ("split_lds_direct_c50", 70, 50, 9, 8, 64, 3, 3, 2, 1),
+    ("split_lds_direct_c50_s1", 33, 50, 6, 7, 96, 3, 3, 1, 1),
+    # 3x3 / stride 2 on three channels: strip kernels of their own
+    ("rgb_3x3_s2", 5, 3, 21, 22, 16, 3, 3, 2, 1),
+    ("rgb_3x3_s2_oc6", 4, 3, 19, 40, 6, 3, 3, 2, 1),
 ]
 
 
@@ -302,6 +323,35 @@ def structured_samples(shape, rng, n_random):
     return np.unique(np.concatenate(idx))
 
 
+# The filter gradient's 128x64 tile: at least 96 output channels, between 128 and 1024 tiles of 64x64 and
+# 8192 pixels to contract, where 64x64 tiles would come to between 4 and 8 workgroups per compute unit (or
+# cannot load straight into LDS).  Batch-innermost order (batch a multiple of 16) and pixel order with every
+# combination of 16-byte / 4-byte loads.  Too large for the full oracle: sampled outputs.
+WIDE_TILE = [
+    ("wide_tile_sweep_shape", 64, 256, 16, 16, 256, 3, 3, 1, 1),
+    ("wide_tile_batch48_5x5", 48, 132, 14, 14, 96, 5, 5, 1, 2),
+    ("wide_tile_pixel_order", 33, 132, 16, 16, 96, 5, 5, 1, 2),
+    ("wide_tile_scalar_dY", 33, 132, 16, 16, 98, 5, 5, 1, 2),
+    ("wide_tile_scalar_X", 33, 130, 16, 16, 96, 5, 5, 1, 2),
+    ("wide_tile_scalar_both", 33, 130, 16, 16, 98, 5, 5, 1, 2),
+]
+
+
+@pytest.mark.parametrize("geo", WIDE_TILE, ids=[g[0] for g in WIDE_TILE])
+def test_wide_filter_gradient_tile_sampled(cks, oracle, geo):
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer(*geo)
+    print("geometry", geo, flush=True)
+    g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, (L.stride,) * 2, (L.padding,) * 2)
+    names = [k for k, _ in cks.cks_plan_hw(cks.CKS_OP_DILATED_CONV2D_WGRAD, *g)]
+    assert names[0].startswith(("pixel_gemm<128, 64,", "pixel_gemm_fast<128, 64,")), names   # the case must not fall to another tile
+    xs, ws, ys = synth.shapes(L)
+    rng = np.random.default_rng(23)
+    samples = (structured_samples(ys, rng, 3000), structured_samples(xs, rng, 3000), structured_samples(ws, rng, 3000))
+    check_layer(cks, oracle, L, seed=300 + [g[0] for g in WIDE_TILE].index(geo[0]), samples=samples)
+
+
 FULL = ["cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4a", "cfg4b"]
 
 
@@ -336,23 +386,37 @@ def test_tensors_beyond_2GiB_sampled(cks, oracle):
 
 
 def test_full_size_cfg1_every_element(cks, oracle):
-    """One benchmark layer compared in full, not sampled (forward and input gradient)."""
+    """One benchmark layer compared in full, not sampled: all three operators, and the input gradient
+    once more in the mode with the filter operations done before the loop (Stage 1, then Stage 2&3 on
+    the split filter)."""
+    import torch
     from paper_2306_15951_amd import synth
 
     L = synth.LAYERS["cfg1"]
     X, W, dY = synth.make_inputs(L, "int", 3)
     Y, dX, dW = run_three(cks, L, X, W, dY)
+    want_dX = oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding)
     assert_exact(Y, oracle.conv_fwd(X, W, L.stride, L.padding), "cfg1 fwd full")
-    assert_exact(dX, oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding), "cfg1 deconv full")
+    assert_exact(dX, want_dX, "cfg1 deconv full")
+    assert_exact(dW, oracle.wgrad(X, dY, L.FH, L.FW, L.stride, L.padding), "cfg1 wgrad full")
+    Cs = nan_like((1, 1, L.IC, L.FH, L.FW, L.OC))
+    dX2 = nan_like(X.shape)
+    cks.cks_kernel_split(dev(W), Cs, 1)
+    cks.cks_deconv2d_presplit(dev(dY), Cs, dX2, L.FH, L.FW, L.stride, L.padding)
+    torch.cuda.synchronize()
+    assert_exact(dX2.cpu().numpy(), want_dX, "cfg1 deconv on the pre-split filter, full")
+
+
+STAGE1 = [(40, 3, 3, 36, 2), (7, 7, 7, 3, 2), (33, 4, 4, 65, 2), (8, 5, 3, 12, 3), (16, 3, 3, 16, 1), (4, 1, 1, 4, 2)]   # OC, FH, FW, IC, stride
 
 
 def test_stage_entry_points(cks, oracle):
     """Stage 1 (kernel split) and the filter transposition against the oracle's
-    data-movement definitions; Stage 2&3 on a pre-split filter equals the fused call."""
+    data-movement definitions."""
     import torch
 
     rng = np.random.default_rng(5)
-    for (OC, FH, FW, IC, s) in [(40, 3, 3, 36, 2), (7, 7, 7, 3, 2), (33, 4, 4, 65, 2), (8, 5, 3, 12, 3), (16, 3, 3, 16, 1), (4, 1, 1, 4, 2)]:
+    for (OC, FH, FW, IC, s) in STAGE1:
         W = rng.standard_normal((OC, FH, FW, IC)).astype(np.float32)
         Wd = dev(W)
         Cs = nan_like((s, s, IC, -(-FH // s), -(-FW // s), OC))
@@ -364,16 +428,51 @@ def test_stage_entry_points(cks, oracle):
         want = np.transpose(oracle.kernel_split(W, s), (0, 1, 5, 3, 4, 2))
         assert np.array_equal(Cs.cpu().numpy().view(np.uint32), want.view(np.uint32)), (OC, FH, FW, IC, s)
         assert np.array_equal(Wt.cpu().numpy(), oracle.filter_transpose(W))
+
+
+# Stage 1 once, Stage 2&3 on the split filter (Section V.A: the filter operations before the loop), with one
+# stride for both axes and per axis: scalar, 16-byte, whole-chunk and LDS-direct loads, narrow and wide tiles
+PRESPLIT = [
+    ("presplit_vec", 40, 12, 9, 8, 20, 3, 3, 2, 1),
+    ("presplit_scalar", 17, 5, 9, 10, 7, 3, 2, 2, 0),
+    ("presplit_lds_direct_wide", 70, 64, 11, 12, 96, 3, 3, 2, 1),
+    ("presplit_lds_direct_narrow", 130, 24, 10, 9, 64, 4, 4, 2, 1),
+    ("presplit_hw_s23", 64, 36, 13, 11, 96, 4, 5, (2, 3), (1, 2)),
+    ("presplit_hw_s31_scalar", 33, 21, 11, 9, 20, 3, 5, (3, 1), (0, 2)),
+    ("presplit_hw_lds_direct", 66, 52, 9, 12, 64, 3, 3, (1, 2), (1, 0)),
+]
+
+
+@pytest.mark.parametrize("geo", PRESPLIT, ids=[g[0] for g in PRESPLIT])
+def test_presplit_mode(cks, oracle, geo):
+    import torch
     from paper_2306_15951_amd import synth
 
-    L = synth.Layer("presplit", 40, 12, 9, 8, 20, 3, 3, 2, 1)
-    X, W, dY = synth.make_inputs(L, "int", 1)
-    Cs = nan_like((2, 2, L.IC, 2, 2, L.OC))
-    dX = nan_like((L.N, L.IH, L.IW, L.IC))
-    cks.cks_kernel_split(dev(W), Cs, 2)
-    cks.cks_deconv2d_presplit(dev(dY), Cs, dX, L.FH, L.FW, 2, 1)
-    torch.cuda.synchronize()
-    assert_exact(dX.cpu().numpy(), oracle.deconv(dY, W, L.IH, L.IW, 2, 1), "presplit")
+    L = synth.Layer(*geo)
+    print("geometry", geo, flush=True)
+    hw = isinstance(L.stride, tuple)
+    (sh, sw), pd = synth.pair(L.stride), synth.pair(L.padding)
+    for kind in ("int", "normal"):
+        X, W, dY = synth.make_inputs(L, kind, 40)
+        Cs = nan_like((sh, sw, L.IC, -(-L.FH // sh), -(-L.FW // sw), L.OC))
+        assert Cs.numel() * 4 == (cks.cks_kernel_split_bytes_hw(L.IC, L.OC, L.FH, L.FW, (sh, sw)) if hw
+                                  else cks.cks_kernel_split_bytes(L.IC, L.OC, L.FH, L.FW, sh))
+        dX = nan_like(X.shape)
+        if hw:
+            cks.cks_kernel_split_hw(dev(W), Cs, (sh, sw))
+            cks.cks_deconv2d_presplit_hw(dev(dY), Cs, dX, L.FH, L.FW, (sh, sw), pd)
+        else:
+            cks.cks_kernel_split(dev(W), Cs, sh)
+            cks.cks_deconv2d_presplit(dev(dY), Cs, dX, L.FH, L.FW, sh, pd[0])
+        torch.cuda.synchronize()
+        want = oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding)
+        if kind == "int":
+            want_Cs = np.transpose(oracle.kernel_split(W, L.stride), (0, 1, 5, 3, 4, 2))
+            assert np.array_equal(Cs.cpu().numpy().view(np.uint32), want_Cs.view(np.uint32)), "Stage 1"
+            assert_exact(dX.cpu().numpy(), want, L.name + " int")
+        else:
+            bound = oracle.deconv(np.abs(dY), np.abs(W), L.IH, L.IW, L.stride, L.padding)
+            assert_close(dX.cpu().numpy(), want, bound, L.name + " normal")
 
 
 GUARD = [
@@ -518,3 +617,29 @@ def test_errors_on_device(cks):
     assert e.value.status == cks.CKS_ERR_WORKSPACE
     with pytest.raises(ValueError):
         cks.cks_conv2d_fwd(X, W, torch.zeros((2, 7, 8, 4), device="cuda"), 1, 1)
+
+
+def planned_calls():
+    """Every call this module makes on the GPU, as (CKS_OP_* number, layer tuple, mask of pointer arguments that
+    are only 4-byte aligned).  tests/test_dispatch_coverage.py asks the library, on the host, which kernels
+    these calls select, and fails if a kernel the library was built with is selected by none of them."""
+    from paper_2306_15951_amd import synth
+
+    FWD, DECONV, WGRAD, SPLIT, PRESPLIT_OP, TRANSPOSE, PARTIALS, REDUCE = range(8)
+    calls = []
+    three = [tuple(synth.LAYERS["cfg0"])] + MID + RANDOM + ASYM + RANDOM_ASYM + WIDE_TILE
+    three += [tuple(synth.LAYERS[n]) for n in FULL] + [("beyond_2GiB", 9, 64, 1024, 1024, 16, 3, 3, 1, 1)]
+    for geo in three:
+        calls += [(op, geo, 0) for op in (FWD, DECONV, WGRAD)]
+    for geo in GUARD:                                    # once aligned, once with every pointer one float off
+        calls += [(op, geo, m) for op in (FWD, DECONV, WGRAD) for m in (0, 15)]
+    calls += [(op, tuple(synth.LAYERS["cfg1"]), 0) for op in (SPLIT, PRESPLIT_OP)]
+    for (OC, FH, FW, IC, s) in STAGE1:
+        calls += [(op, ("stage1", 1, IC, FH, FW, OC, FH, FW, s, 0), 0) for op in (SPLIT, TRANSPOSE)]
+    for geo in PRESPLIT:
+        calls += [(op, geo, 0) for op in (SPLIT, PRESPLIT_OP)]
+    for geo in WGRAD_STAGES:
+        calls += [(op, geo, 0) for op in (PARTIALS, REDUCE)]
+    calls.append((WGRAD, tuple(synth.LAYERS["cfg2"]), 0))
+    calls.append((DECONV, ("stem_repro", 40, 3, 48, 224, 64, 7, 7, 2, 3), 0))
+    return calls
