@@ -53,7 +53,9 @@ typedef enum {
                                  than the padded input, or a tensor of 2^31 or more elements */
     CKS_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than the *_workspace() size */
     CKS_ERR_HIP = -4,         /* a HIP runtime call failed; see cks_last_hip_error() */
-    CKS_ERR_UNSUPPORTED = -5  /* reserved: valid geometry without an implementation */
+    CKS_ERR_UNSUPPORTED = -5, /* reserved: valid geometry without an implementation */
+    CKS_ERR_SCRATCH = -6      /* cks_dilated_conv2d_wgrad_noalloc_hw: the call needs more than
+                                 CKS_STATIC_SCRATCH_BYTES of scratch memory */
 } cks_status;
 
 /* Output size of Eq. (1).  OH, OW may be NULL.  Returns CKS_ERR_SHAPE if the
@@ -142,6 +144,29 @@ int cks_deconv2d_hw(const float *dY, const float *Wt, float *dX,
 int cks_dilated_conv2d_wgrad_hw(const float *X, const float *dY, float *dW,
                                 int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                                 void *ws, size_t ws_bytes, void *stream);
+
+/* ---- for callers that cannot allocate ----
+ *
+ * cks_dilated_conv2d_wgrad_hw for code that must not call hipMalloc and has no
+ * workspace to hand over: work recorded under HIP graph capture, tight serving
+ * or training loops, harnesses that forbid allocation.  Same kernels, same
+ * number of segments and therefore the same bits in dW; the partial sums of
+ * the segments go to a scratch array of CKS_STATIC_SCRATCH_BYTES that is part
+ * of the library's device code: every GPU the library runs on holds its own
+ * copy from the first use until the process ends.  The call allocates and
+ * frees nothing (the first call on a device looks the array's address up).
+ * X, dY in, dW out as for cks_dilated_conv2d_wgrad_hw; inputs and output are
+ * still the caller's.  Returns CKS_ERR_SCRATCH, with nothing enqueued, if the
+ * geometry needs more than CKS_STATIC_SCRATCH_BYTES
+ * (cks_dilated_conv2d_wgrad_workspace_hw tells how much).  All calls on one
+ * GPU share that GPU's array, which keeps the last call's contents (nothing
+ * needs clearing: every partial sum is written before it is read): calls that
+ * overlap in time on one GPU -- on different streams, from different threads
+ * -- race with each other; calls on one stream are ordered and safe. */
+#define CKS_STATIC_SCRATCH_BYTES (32u << 20)
+int cks_dilated_conv2d_wgrad_noalloc_hw(const float *X, const float *dY, float *dW,
+                                        int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                        void *stream);
 
 /* ---- the stages on their own (what the three calls above are made of) ----
  *

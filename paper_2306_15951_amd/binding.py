@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcks.so")
 _lib = None
 
-CKS_OK, CKS_ERR_NULL, CKS_ERR_SHAPE, CKS_ERR_WORKSPACE, CKS_ERR_HIP, CKS_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+CKS_OK, CKS_ERR_NULL, CKS_ERR_SHAPE, CKS_ERR_WORKSPACE, CKS_ERR_HIP, CKS_ERR_UNSUPPORTED, CKS_ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6
+CKS_STATIC_SCRATCH_BYTES = 32 << 20
 (CKS_OP_CONV2D_FWD, CKS_OP_DECONV2D, CKS_OP_DILATED_CONV2D_WGRAD, CKS_OP_KERNEL_SPLIT, CKS_OP_DECONV2D_PRESPLIT,
  CKS_OP_FILTER_TRANSPOSE, CKS_OP_WGRAD_PARTIALS, CKS_OP_REDUCE_PARTIALS) = range(8)
 
@@ -50,6 +51,7 @@ _PROTOTYPES = {
     "cks_deconv2d_presplit_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
     "cks_dilated_conv2d_wgrad_segments_hw": (_GEO_HW, ctypes.c_int),
     "cks_dilated_conv2d_wgrad_partials_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_dilated_conv2d_wgrad_noalloc_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
     "cks_plan_hw": ([ctypes.c_int] + _GEO_HW + [ctypes.c_uint, ctypes.c_char_p, ctypes.c_size_t], ctypes.c_int),
     "cks_strerror": ([ctypes.c_int], ctypes.c_char_p),
     "cks_last_hip_error": ([], ctypes.c_int),
@@ -331,3 +333,14 @@ def cks_plan_hw(op, N, C, H, W, OC, FH, FW, stride, padding, only_4byte_aligned=
         name, _, shape = line.partition(" [")
         out.append((name, "[" + shape))
     return out
+
+
+def cks_dilated_conv2d_wgrad_noalloc_hw(X, dY, dW, stride, padding):
+    """dW <- Sk-dilated-V2(X, dY) with the partial sums in the library's static scratch array."""
+    N, H, W, C = X.shape
+    OC, FH, FW, _ = dW.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    _check(lib().cks_dilated_conv2d_wgrad_noalloc_hw(_ptr(X, "X"), _ptr(dY, "dY", (N, OH, OW, OC)), _ptr(dW, "dW", (OC, FH, FW, C)),
+                                                     N, C, H, W, OC, FH, FW, *stride, *padding, _stream()),
+           "cks_dilated_conv2d_wgrad_noalloc_hw")
+    return dW

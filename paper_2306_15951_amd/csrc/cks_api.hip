@@ -6,6 +6,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <set>
@@ -21,6 +22,11 @@
 #include "cks_scatter_deconv.h"
 #include "cks_strip_fwd.h"
 #include "cks_strip_wgrad.h"
+
+// Scratch memory of cks_dilated_conv2d_wgrad_noalloc_hw: one array per GPU, part of the loaded code object,
+// held until the process ends.  In host code the array's name only stands for the symbol; its device
+// address is looked up once per device (static_scratch) and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[CKS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -96,6 +102,31 @@ inline hipError_t allow_large_lds(const void *kernel)
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess) done.insert({kernel, dev});
     return e;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up on the first call per device.
+constexpr int kMaxDevices = 64;
+int static_scratch(void **out)
+{
+    static std::mutex mu;
+    static std::atomic<void *> known[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return CKS_ERR_UNSUPPORTED;
+    void *p = known[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(mu);
+        p = known[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return hip_fail(e);
+            if (!p) return CKS_ERR_UNSUPPORTED;
+            known[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return CKS_OK;
 }
 
 // A kernel's name as the demangler prints its instantiation, e.g. "rowrun_gemm_dma<2, 64, 64, 2, 2>":
@@ -882,6 +913,25 @@ int cks_dilated_conv2d_wgrad_hw(const float *X, const float *dY, float *dW,
     return wgrad(g, X, dY, dW, ws, ws_bytes, stream);
 }
 
+int cks_dilated_conv2d_wgrad_noalloc_hw(const float *X, const float *dY, float *dW,
+                                        int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                        void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    if (!X || !dY || !dW) return CKS_ERR_NULL;
+    const size_t need = wgrad_workspace(g);
+    if (need > CKS_STATIC_SCRATCH_BYTES) return CKS_ERR_SCRATCH;
+    void *ptr = nullptr;
+    if (need > 0 && !g_plan) {
+        rc = static_scratch(&ptr);
+        if (rc != CKS_OK) return rc;
+    }
+    // every element of the partial sums is written before the aggregation reads it: nothing to clear
+    return wgrad(g, X, dY, dW, ptr, need, stream);
+}
+
 // ---- one stride and one padding for both axes
 
 int cks_out_dims(int H, int W, int FH, int FW, int stride, int padding, int *OH, int *OW)
@@ -1064,6 +1114,7 @@ const char *cks_strerror(int status)
         case CKS_ERR_WORKSPACE: return "workspace missing or too small";
         case CKS_ERR_HIP: return "HIP runtime error (see cks_last_hip_error)";
         case CKS_ERR_UNSUPPORTED: return "geometry not supported";
+        case CKS_ERR_SCRATCH: return "the call needs more scratch memory than the library's static buffer holds";
         default: return "unknown status";
     }
 }

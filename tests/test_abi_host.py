@@ -140,3 +140,18 @@ def test_per_axis_entry_points_on_the_host(cks, oracle):
         assert cks.cks_useful_macs_hw(*g) == oracle.mac_counts(*g)["useful"], g
     g = (3, 2, 6, 9, 5, 3, 4, 2, 1)
     assert cks.cks_useful_macs_hw(*g[:7], (2, 2), (1, 1)) == cks.cks_useful_macs(*g)
+
+
+def test_no_alloc_entry_point_checks_its_limit_on_the_host(cks):
+    """cks_dilated_conv2d_wgrad_noalloc_hw refuses, before any device call, a geometry whose partial sums
+    exceed the static scratch array."""
+    L = cks.lib()
+    fake = ctypes.c_void_p(0x1000)
+    big = (256, 512, 7, 7, 512, 3, 3, 1, 1, 1, 1)
+    assert L.cks_dilated_conv2d_wgrad_workspace_hw(*big) > cks.CKS_STATIC_SCRATCH_BYTES
+    assert L.cks_dilated_conv2d_wgrad_noalloc_hw(fake, fake, fake, *big, None) == cks.CKS_ERR_SCRATCH
+    assert L.cks_dilated_conv2d_wgrad_noalloc_hw(fake, None, fake, *big, None) == cks.CKS_ERR_NULL
+    assert L.cks_dilated_conv2d_wgrad_noalloc_hw(fake, fake, fake, 256, 512, 7, 7, 512, 3, 3, 1, 0, 1, 1, None) == cks.CKS_ERR_SHAPE
+    assert b"static" in L.cks_strerror(cks.CKS_ERR_SCRATCH)
+    text = open(os.path.join(ROOT, "include", "cks.h")).read()
+    assert "#define CKS_STATIC_SCRATCH_BYTES (32u << 20)" in text and cks.CKS_STATIC_SCRATCH_BYTES == 32 << 20
