@@ -1,18 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the C-K-S conv-layer hot path on one MI355X.
 
-A step = one pass of the whole hot path over one synthetic batch of a layer:
-ConvV2 forward, KS-deconv-V2 input gradient (kernel split + Stage 2&3) and
-Sk-dilated-V2 filter gradient (segments + reduction), inputs resident in HBM.
-Prints ONE JSON line: useful (zero-free) TFLOP/s of the step, the roofline of
-the dominant kernel measured with events on the launch stream, and the CPU
-oracle timed on a bounded sample of the same workload.
+A step = one pass of the whole hot path over one synthetic batch of a layer: ConvV2 forward, KS-deconv-V2
+input gradient and Sk-dilated-V2 filter gradient (segments + aggregation), inputs resident in HBM.  The
+default run times every benchmark layer (cfg1 ... cfg4b) and prints ONE JSON line:
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg1] [--all]
+  value / ms_per_step   the step on the headline layer (--config, default cfg3a: the largest layer by
+                        useful FLOPs), exactly --steps steps between two events, median of --repeats
+  configs               per layer: step and per-operator ms (median and min of the repeats), useful
+                        TFLOP/s, % of the fp32 matrix peak, the kernels each call launches, the
+                        main kernels' own launch times, the input gradient with the filter split
+                        beforehand (Section V.A, pack excluded / included), and that layer's roofline
+  min_pct_fp32_mfma_peak the lowest per-operator figure over all layers, with the layer and operator
+  roofline              the headline layer's dominant kernel against 157.3 TFLOP/s
+  cpu_baseline          the CPU oracle on a bounded sample of the headline layer
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3a] [--layers cfg1,cfg2,...]
+    python bench.py --ablation | --sweep | --mfma-probe | --copy-probe
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -21,6 +30,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak
 METRIC = "useful TFLOPS per operator (ConvV2 / KS-deconv / Sk-dilated), % fp32 MFMA peak"
+BENCH_LAYERS = ["cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4a", "cfg4b"]
+SETTLE_MS = 250.0               # load put on the GPU before a layer is timed, whatever --warmup says
+OPS = ("conv2d_fwd", "deconv2d", "dilated_conv2d_wgrad")
 
 
 def describe(L):
@@ -38,6 +50,7 @@ class LayerBench:
 
         self.L, self.cks, self.torch = L, cks, torch
         self.g = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, L.stride, L.padding)
+        self.g_hw = (L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, (L.stride,) * 2, (L.padding,) * 2)
         self.host = synth.make_inputs(L, "normal", seed)
         X, W, dY = self.host
         d = "cuda:0"
@@ -52,6 +65,10 @@ class LayerBench:
         self.Cs = torch.empty((s, s, L.IC, -(-L.FH // s), -(-L.FW // s), L.OC), device=d)
         self.part = torch.empty((self.gz, L.OC, L.FH, L.FW, L.IC), device=d)
         self.useful_flops = 2 * cks.cks_useful_macs(*self.g)
+
+    def plan(self, op):
+        """Names of the kernels entry point `op` launches for this layer (host-side query of the library)."""
+        return [k for k, _ in self.cks.cks_plan_hw(op, *self.g_hw)]
 
     # the three operators as a user calls them
     def fwd(self):
@@ -68,11 +85,11 @@ class LayerBench:
         self.deconv()
         self.wgrad()
 
-    # single kernels (stage entry points)
+    # single stages (stage entry points)
     def k_split(self):
         self.cks.cks_kernel_split(self.W, self.Cs, self.L.stride)
 
-    def k_deconv_main(self):
+    def k_deconv_presplit(self):
         self.cks.cks_deconv2d_presplit(self.dY, self.Cs, self.dX, self.L.FH, self.L.FW, self.L.stride, self.L.padding)
 
     def k_wgrad_main(self):
@@ -82,48 +99,66 @@ class LayerBench:
     def k_reduce(self):
         self.cks.cks_reduce_partials(self.part, self.dW)
 
-    def time_ms(self, fn, iters, warmup):
-        """Average milliseconds per call: events on the stream the library launches on."""
+    def settle(self, ms=SETTLE_MS):
+        """Keep the GPU under this layer's load for `ms`: after an idle spell (allocating and filling the
+        tensors is one) the board needs some tens of milliseconds before timings are steady."""
+        torch = self.torch
+        busy, batch = 0.0, 3
+        while busy < ms:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(batch):
+                self.step()
+            e1.record()
+            torch.cuda.synchronize()
+            t = max(e0.elapsed_time(e1), 1e-3)
+            busy += t
+            batch = max(3, min(int(batch * 50.0 / t), 2000))      # batches of about 50 ms
+
+    def time_ms(self, fn, iters, warmup, repeats=1):
+        """Milliseconds per call, one figure per repeat: `iters` calls between two events on the stream the
+        library launches on (torch's current stream is the one handed to it), a device sync on both sides."""
         torch = self.torch
         for _ in range(warmup):
             fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()          # torch's current stream == the stream handed to the library
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        out = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / iters)
+        return out
 
 
-def measured_traffic(workload, kernel_prefix):
-    """HBM bytes per launch of a kernel, from the committed rocprofv3 counter
-    summary of this workload (profiles/bench_<workload>_traffic.txt), or None."""
-    path = os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % workload)
+def hbm_traffic(layer, kernel):
+    """HBM bytes per launch of `kernel` on `layer` from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic.txt: FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a copy kernel of
+    known size), or None.  Not a measurement of the present run."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
-        if line.startswith("#"):
-            continue
         f = line.rstrip("\n").split("\t")
-        if len(f) == 3 and f[0].startswith(kernel_prefix):
-            return float(f[1]) + float(f[2])
+        if len(f) == 4 and f[0] == layer and f[1].replace(" ", "") == kernel.replace(" ", ""):
+            return float(f[2]) + float(f[3])
     return None
 
 
 def mfma_probe(fn=None, busy_ms=30.0):
-    """What the fp32 matrix cores sustain on this machine (libcks_probe.so, include/cks_probe.h), each case run
-    back to back for busy_ms after 20 ms of the same load, with the shader clock sampled from a second
-    stream meanwhile.  With fn (a callable that launches work on the current stream) only the clock under
-    that load is measured."""
+    """What the fp32 matrix cores sustain on this machine (bench_probe/libcks_probe.so), each case run back to
+    back for busy_ms after 20 ms of the same load, with the shader clock sampled from a second stream
+    meanwhile.  With fn (a callable that launches work on the current stream) only the clock under that
+    load is measured."""
     import ctypes
-    import numpy as np
     import torch
 
-    path = os.path.join(ROOT, "paper_2306_15951_amd", "libcks_probe.so")
+    path = os.path.join(ROOT, "bench_probe", "libcks_probe.so")
     if not os.path.exists(path):
-        raise ImportError("libcks_probe.so is not built: run __graft_entry__.build()")
+        raise ImportError("bench_probe/libcks_probe.so is not built: run __graft_entry__.build()")
     P = ctypes.CDLL(path)
     vp, ci = ctypes.c_void_p, ctypes.c_int
     P.cks_probe_mfma_registers.argtypes = [vp, ci, ci, ci, vp]
@@ -171,8 +206,8 @@ def mfma_probe(fn=None, busy_ms=30.0):
 
 
 def cpu_baseline(L, host, useful_flops, budget_s=6.0):
-    """The oracle as it stands, on a random sample of outputs of each operator,
-    sized from a short calibration so that each operator takes about budget_s."""
+    """The oracle as it stands, on a random sample of outputs of each operator (indices drawn with
+    replacement), sized from a short calibration so that each operator takes about budget_s."""
     import numpy as np
     import oracle
 
@@ -194,33 +229,63 @@ def cpu_baseline(L, host, useful_flops, budget_s=6.0):
         secs += dt
         parts.append("%s %d of %d outputs in %.2fs" % (name, n, size, dt))
     return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "; ".join(parts) + " (random output elements, useful FLOPs pro rata, "
-                      "time includes building the padded / zero-inserted tensors)"}
+            "sample": "%s: " % L.name + "; ".join(parts) + " (random output elements drawn with replacement, useful FLOPs "
+                      "pro rata, time includes building the padded / zero-inserted tensors)"}
 
 
-def bench_layer(L, steps, warmup, with_kernels=True):
+def pct(tflops):
+    return 100.0 * tflops / PEAK_FP32_MFMA_TFLOPS
+
+
+def timing(ms_list, flops):
+    med, lo = statistics.median(ms_list), min(ms_list)
+    tf = flops / med / 1e9
+    return {"ms_median": med, "ms_min": lo, "useful_tflops": tf, "pct_fp32_mfma_peak": pct(tf),
+            "pct_fp32_mfma_peak_best": pct(flops / lo / 1e9)}
+
+
+def bench_layer(L, steps, warmup, repeats, settle_ms=SETTLE_MS):
+    """All timings of one layer.  Returns (LayerBench, dict)."""
     B = LayerBench(L)
-    out = {"useful_gflop_per_operator": B.useful_flops / 1e9, "segments_G_Z": B.gz}
-    ms_step = B.time_ms(B.step, steps, warmup)
-    out["ms_per_step"] = ms_step
-    out["step_tflops"] = 3 * B.useful_flops / ms_step / 1e9
+    cks = B.cks
+    out = {"workload": describe(L), "useful_gflop_per_operator": B.useful_flops / 1e9, "segments_G_Z": B.gz}
+    B.settle(settle_ms)
+    out["step"] = timing(B.time_ms(B.step, steps, warmup, repeats), 3 * B.useful_flops)
     ops = {}
-    for name, fn in (("conv2d_fwd", B.fwd), ("deconv2d", B.deconv), ("dilated_conv2d_wgrad", B.wgrad)):
-        ms = B.time_ms(fn, steps, warmup)
-        tf = B.useful_flops / ms / 1e9
-        ops[name] = {"ms": ms, "useful_tflops": tf, "pct_fp32_mfma_peak": 100 * tf / PEAK_FP32_MFMA_TFLOPS}
+    for name, fn, op in (("conv2d_fwd", B.fwd, cks.CKS_OP_CONV2D_FWD), ("deconv2d", B.deconv, cks.CKS_OP_DECONV2D),
+                         ("dilated_conv2d_wgrad", B.wgrad, cks.CKS_OP_DILATED_CONV2D_WGRAD)):
+        ops[name] = timing(B.time_ms(fn, steps, warmup, repeats), B.useful_flops)
+        ops[name]["kernels"] = B.plan(op)
     out["operators"] = ops
-    if with_kernels:
-        B.k_split(); B.k_wgrad_main()
-        ker = {}
-        # the step's own kernels (cfg1: one launch each for forward and input gradient, which reads the
-        # filter in place; main + reduce for the filter gradient) and the stage entry points of the
-        # pre-split mode (kernel split, Stage 2&3 on a split filter)
-        for name, fn in (("rowrun_gemm<fwd>", B.fwd), ("rowrun_gemm<deconv>", B.deconv), ("pixel_gemm", B.k_wgrad_main),
-                         ("reduce_slices", B.k_reduce), ("pack_filter<split>", B.k_split),
-                         ("rowrun_gemm<deconv, presplit>", B.k_deconv_main)):
-            ker[name] = B.time_ms(fn, steps, warmup)
-        out["kernel_ms"] = ker
+    # Main kernels on their own.  Forward and input gradient are one main launch each (the few-channel input
+    # gradient adds a short second one, timed with it); the filter gradient's main kernel and its aggregation
+    # are timed through the stage entry points.  These are event timings of back-to-back launches, so each
+    # includes the gap between two launches (3-5 us) that a profiler's kernel duration does not.
+    B.k_wgrad_main()
+    mains = {
+        ops["conv2d_fwd"]["kernels"][0]: ops["conv2d_fwd"]["ms_median"],
+        ops["deconv2d"]["kernels"][0]: ops["deconv2d"]["ms_median"],
+        B.plan(cks.CKS_OP_WGRAD_PARTIALS)[0]: statistics.median(B.time_ms(B.k_wgrad_main, steps, warmup, repeats)),
+    }
+    out["main_kernels"] = {k: {"ms": v, "useful_tflops": B.useful_flops / v / 1e9, "frac_of_peak": B.useful_flops / v / 1e9 / PEAK_FP32_MFMA_TFLOPS}
+                           for k, v in mains.items()}
+    if B.gz > 1:
+        out["reduce_slices_ms"] = statistics.median(B.time_ms(B.k_reduce, steps, warmup, repeats))
+    # The filter operations done before the loop (Section V.A): Stage 1 once, Stage 2&3 on the split filter.
+    B.k_split()
+    split_ms = statistics.median(B.time_ms(B.k_split, steps, warmup, repeats))
+    pre_ms = statistics.median(B.time_ms(B.k_deconv_presplit, steps, warmup, repeats))
+    out["deconv2d_filter_split_beforehand"] = {
+        "kernel_split_ms": split_ms, "stage2and3_ms": pre_ms, "kernels": B.plan(cks.CKS_OP_DECONV2D_PRESPLIT),
+        "pct_fp32_mfma_peak_pack_excluded": pct(B.useful_flops / pre_ms / 1e9),
+        "pct_fp32_mfma_peak_pack_included": pct(B.useful_flops / (pre_ms + split_ms) / 1e9),
+    }
+    dom = max(mains, key=mains.get)
+    achieved = B.useful_flops / mains[dom] / 1e9
+    out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                       "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": hbm_traffic(L.name, dom),
+                       "traffic_unit": "HBM bytes per launch, read from profiles/hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE "
+                                       "of an earlier run of this script; not measured in this run)"}
     return B, out
 
 
@@ -235,15 +300,7 @@ SWEEP = (
 )
 
 
-def warm_gpu():
-    """Half a second of the cfg1 step, so that short timings that follow run at the sustained clock."""
-    from paper_2306_15951_amd import synth
-
-    B = LayerBench(synth.LAYERS["cfg1"])
-    B.time_ms(B.step, 1500, 10)
-
-
-def sweep(steps, warmup):
+def sweep(steps, warmup, repeats):
     """Useful TFLOP/s of the three operators over the SWEEP shapes."""
     import torch
     from paper_2306_15951_amd import synth
@@ -251,10 +308,11 @@ def sweep(steps, warmup):
     rows = {}
     for geo in SWEEP:
         B = LayerBench(synth.Layer(*geo))
+        B.settle()
         r = {}
         for name, fn in (("conv2d_fwd", B.fwd), ("deconv2d", B.deconv), ("dilated_conv2d_wgrad", B.wgrad)):
-            ms = B.time_ms(fn, steps, warmup)
-            r[name] = {"ms": ms, "pct_fp32_mfma_peak": 100 * B.useful_flops / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS}
+            t = timing(B.time_ms(fn, steps, warmup, repeats), B.useful_flops)
+            r[name] = {"ms": t["ms_median"], "pct_fp32_mfma_peak": t["pct_fp32_mfma_peak"]}
         rows[geo[0]] = {"geometry": geo[1:], "useful_gflop": B.useful_flops / 1e9, "operators": r}
         del B
         torch.cuda.empty_cache()
@@ -262,35 +320,55 @@ def sweep(steps, warmup):
 
 
 def ablation(L, steps, warmup):
-    """Skipping zeros against multiplying them, with the same kernels: each operator is also run in
-    its textbook form on tensors with the zeros written out (padding border; stride-inserted zeros
-    + rotated filter; dilated gradient), through cks_conv2d_fwd with padding 0."""
+    """What each zero-skipping step is worth, per operator, with the library's own kernels throughout:
+
+      skip       the operator as the library runs it (ConvV2, KS-deconv-V2, Sk-dilated-V2)
+      untrimmed  trimming off, kernel split / leaping access kept: plain convolution, KS-deconv
+                 (Algorithm 2), Sk-dilated (Algorithm 3) -- the same entry points on tensors whose zero
+                 border is written out (paper_2306_15951_amd/untrimmed.py)
+      dense      the textbook form that multiplies every zero: padded input; stride-inserted zeros on a
+                 canvas + rotated filter at unit stride; the dilated gradient as a filter -- all through
+                 cks_conv2d_fwd with padding 0
+    """
     import torch
     import torch.nn.functional as F
+    from paper_2306_15951_amd import untrimmed
 
     B = LayerBench(L)
+    B.settle()
     cks, s, p = B.cks, L.stride, L.padding
     OH, OW = cks.cks_out_dims(L.IH, L.IW, L.FH, L.FW, s, p)
-    out = {"useful_gflop": B.useful_flops / 1e9}
+    out = {"useful_gflop": B.useful_flops / 1e9, "dense_gflop": 2e-9 * cks.cks_useful_macs(L.N, L.IC, L.IH + 2 * p, L.IW + 2 * p, L.OC, L.FH, L.FW, s, 0)}
 
-    def timed_pair(skip, dense):
-        # alternate the two forms three times and keep each one's best: buffers run slower for their
-        # first launches and the order of measurement must not decide a 5 % difference
-        ts, td = [], []
+    def timed(fns):
+        # alternate the forms three times and keep each one's best: buffers run slower for their first
+        # launches and the order of measurement must not decide a 5 % difference
+        best = [float("inf")] * len(fns)
         for _ in range(3):
-            ts.append(B.time_ms(skip, steps, warmup))
-            td.append(B.time_ms(dense, steps, warmup))
-        return {"skip_ms": min(ts), "dense_ms": min(td)}
+            for i, fn in enumerate(fns):
+                best[i] = min(best[i], B.time_ms(fn, steps, warmup)[0])
+        return best
 
     def close(a, b):
         return float((a - b).abs().max() / max(float(b.abs().max()), 1e-30))
 
-    # ConvV2 | padded input, padding 0
+    def row(skip, untrim, dense, got_untrim, got_dense, want):
+        skip(); untrim(); dense()
+        torch.cuda.synchronize()
+        d = {"max_rel_diff_untrimmed": close(got_untrim(), want()), "max_rel_diff_dense": close(got_dense(), want())}
+        d["skip_ms"], d["untrimmed_ms"], d["dense_ms"] = timed((skip, untrim, dense))
+        d["gain_of_trimming"] = d["untrimmed_ms"] / d["skip_ms"]
+        d["gain_over_dense"] = d["dense_ms"] / d["skip_ms"]
+        return d
+
+    # ConvV2 | plain convolution = the dense form: the padded input, padding 0
     Xp = F.pad(B.X, (0, 0, p, p, p, p)).contiguous()
     Y2 = torch.empty_like(B.Y)
-    B.fwd(); cks.cks_conv2d_fwd(Xp, B.W, Y2, s, 0)
-    out["conv2d_fwd"] = dict(timed_pair(B.fwd, lambda: cks.cks_conv2d_fwd(Xp, B.W, Y2, s, 0)), max_rel_diff=close(Y2, B.Y))
-    # KS-deconv | zero-inserted gradient on a zero canvas, rotated filter, unit stride
+    plain = lambda: cks.cks_conv2d_fwd(Xp, B.W, Y2, s, 0)
+    out["conv2d_fwd"] = row(B.fwd, plain, plain, lambda: Y2, lambda: Y2, lambda: B.Y)
+    # KS-deconv-V2 | KS-deconv (Algorithm 2) | zero-inserted gradient on a zero canvas, rotated filter, unit stride
+    dX1 = torch.empty_like(B.dX)
+    alg2 = untrimmed.prepare_deconv2d(cks, B.dY, B.W, dX1, s, p)
     Z = torch.zeros((L.N, L.IH + L.FH - 1, L.IW + L.FW - 1, L.OC), device=B.X.device)
     o = (L.FH - 1 - p, L.FW - 1 - p)
     hs, ws = (OH - 1) * s + 1, (OW - 1) * s + 1
@@ -300,36 +378,36 @@ def ablation(L, steps, warmup):
     Z[:, ih[mh][:, None], iw[mw][None, :], :] = B.dY[:, mh][:, :, mw]
     Wr = B.W.flip(1, 2).permute(3, 1, 2, 0).contiguous()      # [IC, FH, FW, OC]
     dX2 = torch.empty_like(B.dX)
-    B.deconv(); cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0)
-    out["deconv2d"] = dict(timed_pair(B.deconv, lambda: cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0)), max_rel_diff=close(dX2, B.dX))
-    # Sk-dilated | dilated gradient as the filter of a unit-stride convolution over the padded input
-    # (image axis and channel axis change places: the contraction runs over n)
+    out["deconv2d"] = row(B.deconv, alg2, lambda: cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0), lambda: dX1, lambda: dX2, lambda: B.dX)
+    # Sk-dilated-V2 | Sk-dilated (Algorithm 3) | the dilated gradient as the filter of a unit-stride convolution
+    # over the padded input (image axis and channel axis change places: the contraction runs over n)
+    dW1 = torch.empty_like(B.dW)
+    alg3 = untrimmed.prepare_dilated_conv2d_wgrad(cks, B.X, B.dY, dW1, s, p)
     D = torch.zeros((L.N, hs, ws, L.OC), device=B.X.device)
     D[:, ::s, ::s, :] = B.dY
     need_h, need_w = hs + L.FH - 1, ws + L.FW - 1                    # padded rows the FH x FW output uses
     Xq = Xp[:, :need_h, :need_w, :].permute(3, 1, 2, 0).contiguous()   # [IC, rows, cols, N]
     Dq = D.permute(3, 1, 2, 0).contiguous()                            # [OC, hs, ws, N]
     dWq = torch.empty((L.IC, L.FH, L.FW, L.OC), device=B.X.device)
-    B.wgrad(); cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0)
-    out["dilated_conv2d_wgrad"] = dict(timed_pair(B.wgrad, lambda: cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0)),
-                                       max_rel_diff=close(dWq.permute(3, 1, 2, 0), B.dW))
-    for v in out.values():
-        if isinstance(v, dict):
-            v["speedup"] = v["dense_ms"] / v["skip_ms"]
+    out["dilated_conv2d_wgrad"] = row(B.wgrad, alg3, lambda: cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0),
+                                      lambda: dW1, lambda: dWq.permute(3, 1, 2, 0), lambda: B.dW)
     return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=200)   # the box needs some tens of milliseconds of load to reach its steady state
-    ap.add_argument("--config", default="cfg1")
-    ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (extra JSON field)")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20, help="untimed calls before each timed series (on top of %.0f ms of load per layer)" % SETTLE_MS)
+    ap.add_argument("--repeats", type=int, default=5, help="timed series of --steps calls each; median and min are reported")
+    ap.add_argument("--config", default="cfg3a", help="headline layer (value, ms_per_step, roofline, cpu_baseline)")
+    ap.add_argument("--layers", default=",".join(BENCH_LAYERS), help="layers to time (the headline layer is always included)")
+    ap.add_argument("--settle-ms", type=float, default=SETTLE_MS, help="load put on the GPU before a layer is timed (profiler runs use less)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the sustained-rate / clock probes")
     ap.add_argument("--sweep", action="store_true", help="only: the three operators over a sweep of invented shapes")
     ap.add_argument("--ablation", action="store_true",
-                    help="only: zeros skipped against zeros multiplied, same kernels, on the benchmark layers")
+                    help="only: zeros skipped / trimming off / zeros multiplied, same kernels, on the benchmark layers")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="only: the fp32 matrix rate this box sustains (registers / LDS-fed loop, constant / varying operands)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -355,66 +433,66 @@ def main():
                           "bytes_written_per_launch": 4 * n, "launches": 5}))
         return
     if a.mfma_probe:
-        warm_gpu()
+        LayerBench(synth.LAYERS["cfg1"]).settle(500.0)
         print(json.dumps({"mfma_probe": mfma_probe(), "unit": "TFLOP/s", "published_peak": PEAK_FP32_MFMA_TFLOPS}))
         return
-    if a.sweep or a.ablation:
-        warm_gpu()
     if a.sweep:
-        # freshly allocated buffers run slower for their first ~60 launches: long warm-up per operator
-        print(json.dumps({"sweep": sweep(max(a.steps // 2, 10), max(3 * a.warmup, 60)), "data": "synthetic, invented shapes"}))
+        print(json.dumps({"sweep": sweep(a.steps, a.warmup, a.repeats), "steps": a.steps, "warmup": a.warmup,
+                          "repeats": a.repeats, "data": "synthetic, invented shapes"}))
         return
     if a.ablation:
         res = {}
         for name in ("cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4a"):
-            res[name] = ablation(synth.LAYERS[name], max(a.steps // 4, 10), max(2 * a.warmup, 40))
+            res[name] = ablation(synth.LAYERS[name], a.steps, a.warmup)
             torch.cuda.empty_cache()
-        print(json.dumps({"ablation": res, "data": "synthetic"}))
+        print(json.dumps({"ablation": res, "steps": a.steps, "warmup": a.warmup, "data": "synthetic"}))
         return
-    L = synth.LAYERS[a.config]
-    B, r = bench_layer(L, a.steps, a.warmup)
 
-    # dominant kernel of the step = the main kernel with the longest average launch
-    mains = {k: r["kernel_ms"][k] for k in ("rowrun_gemm<fwd>", "rowrun_gemm<deconv>", "pixel_gemm")}
-    dom = max(mains, key=mains.get)
-    achieved = B.useful_flops / mains[dom] / 1e9
-    # (kernel names as the profiler prints them: the variants that load their chunks straight into LDS)
-    prefix = {"rowrun_gemm<fwd>": "cks::rowrun_gemm_dma<0", "rowrun_gemm<deconv>": "cks::rowrun_gemm_dma<2",
-              "pixel_gemm": "cks::pixel_gemm_dma"}[dom]
+    names = [n for n in a.layers.split(",") if n]
+    if a.config not in names:
+        names.append(a.config)
+    configs, head = {}, None
+    for name in names:
+        B, r = bench_layer(synth.LAYERS[name], a.steps, a.warmup, a.repeats, a.settle_ms)
+        configs[name] = r
+        if name == a.config:
+            head = (B.L, B.host, B.useful_flops)
+            if not a.no_probe:
+                k = r["roofline"]["kernel"]
+                fn = B.fwd if k == r["operators"]["conv2d_fwd"]["kernels"][0] else (
+                    B.deconv if k == r["operators"]["deconv2d"]["kernels"][0] else B.k_wgrad_main)
+                r["roofline"]["clock_under_dominant_kernel"] = mfma_probe(fn)
+        del B
+        torch.cuda.empty_cache()
+    H = configs[a.config]
+    lowest = min(((r["operators"][op]["pct_fp32_mfma_peak"], name, op) for name, r in configs.items() for op in OPS))
     line = {
-        "metric": METRIC, "value": r["step_tflops"], "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": a.steps, "warmup": a.warmup, "ms_per_step": r["ms_per_step"],
+        "metric": METRIC, "value": H["step"]["useful_tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": H["step"]["ms_median"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": describe(L), "step": "conv2d_fwd + deconv2d + dilated_conv2d_wgrad",
-                   "useful_gflop_per_operator": r["useful_gflop_per_operator"], "segments_G_Z": r["segments_G_Z"]},
-        "pct_fp32_mfma_peak": 100 * r["step_tflops"] / PEAK_FP32_MFMA_TFLOPS,
-        "operators": r["operators"], "kernel_ms": r["kernel_ms"],
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": measured_traffic(a.config, prefix), "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE)",
-                     "all_main_kernels": {k: B.useful_flops / v / 1e9 for k, v in mains.items()}},
+        "config": {"workload": H["workload"], "step": "conv2d_fwd + deconv2d + dilated_conv2d_wgrad",
+                   "useful_gflop_per_operator": H["useful_gflop_per_operator"], "segments_G_Z": H["segments_G_Z"],
+                   "timing": "median of %d series of %d steps, each after %d untimed steps; %.0f ms of load per layer first"
+                             % (a.repeats, a.steps, a.warmup, a.settle_ms)},
+        "pct_fp32_mfma_peak": H["step"]["pct_fp32_mfma_peak"],
+        "min_pct_fp32_mfma_peak": {"value": lowest[0], "layer": lowest[1], "operator": lowest[2],
+                                   "over": "every operator of " + ", ".join(configs)},
+        "pct_fp32_mfma_peak_by_layer": {name: {op: round(r["operators"][op]["pct_fp32_mfma_peak"], 2) for op in OPS}
+                                        for name, r in configs.items()},
+        "roofline": dict(H["roofline"]),
+        "configs": configs,
     }
-    # the same rate against what the matrix cores sustain here with operands that vary (the published peak
-    # assumes back-to-back issue at 2.4 GHz), and the shader clock while the dominant kernel runs
-    probe = mfma_probe()
-    sustained = probe["lds_fed_k_loop_varying_operands"]["tflops"]
-    line["roofline"]["peak_sustained"] = {
-        "what": "fp32 MFMA rate measured on this box, TFLOP/s: LDS-fed K loop of the general kernels without its global side / registers only; constant / varying operands",
-        "probe": probe, "frac_of_lds_fed_varying": achieved / sustained,
-        "clock_under_dominant_kernel": mfma_probe({"rowrun_gemm<fwd>": B.fwd, "rowrun_gemm<deconv>": B.deconv, "pixel_gemm": B.k_wgrad_main}[dom]),
-    }
+    if not a.no_probe:
+        # the same rate against what the matrix cores sustain here with operands that vary (the published
+        # peak assumes back-to-back issue at 2.4 GHz)
+        probe = mfma_probe()
+        line["roofline"]["peak_sustained"] = {
+            "what": "fp32 MFMA rate measured on this box, TFLOP/s: LDS-fed K loop of the general kernels without its global "
+                    "side / registers only; constant / varying operands",
+            "probe": probe,
+            "frac_of_lds_fed_varying": H["roofline"]["achieved"] / probe["lds_fed_k_loop_varying_operands"]["tflops"]}
     if not a.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(L, B.host, B.useful_flops)
-    if a.all:
-        others = {}
-        for name in synth.LAYERS:
-            if name in (a.config, "cfg0"):
-                continue
-            del B
-            torch.cuda.empty_cache()
-            B, rr = bench_layer(synth.LAYERS[name], max(a.steps // 2, 10), max(a.warmup, 100))
-            others[name] = rr
-        line["other_configs"] = others
+        line["cpu_baseline"] = cpu_baseline(*head)
     print(json.dumps(line))
 
 

@@ -1,5 +1,6 @@
 /*
- * cks_probe.h -- measurement probes used by bench.py (libcks_probe.so), not part of the operators.
+ * cks_probe.h -- measurement probes used by bench.py (bench_probe/libcks_probe.so); not part of the
+ * operators' library, its headers or its source tree.
  *
  * The operators of cks.h are bound by the fp32 matrix cores.  The published peak (157.3 TFLOP/s) assumes
  * every matrix instruction issues back to back at 2.4 GHz; what the chip sustains depends on the operand

@@ -1,7 +1,7 @@
 // Measurement probes for the benchmark (not part of the operators' path): what the fp32 matrix cores of
 // this chip sustain with operands that are not constants, and the shader clock while a kernel runs.
-// Built into libcks_probe.so; see include/cks_probe.h.
-#include "../../include/cks_probe.h"
+// Built into bench_probe/libcks_probe.so by the package's build step; see cks_probe.h.
+#include "cks_probe.h"
 
 #include <hip/hip_runtime.h>
 

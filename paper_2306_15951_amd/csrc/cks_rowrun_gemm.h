@@ -21,8 +21,8 @@
 //
 // So a workgroup owns (position, 128/64 batch rows, 128/64/32 channels), knows its
 // trim as scalars, and walks  nruns x ceil(L/32)  K-chunks; trimming costs
-// nothing but two pointer offsets and a shorter loop (Section IV.A: "moving
-// pointers and restricting memory-access"), no lane ever multiplies a padded
+// nothing but two pointer offsets and a shorter loop (the realisation of
+// trimming that Section IV.A describes), no lane ever multiplies a padded
 // or inserted zero, and no per-element bounds test exists in the loop.
 #pragma once
 #include "cks_device.h"

@@ -19,7 +19,11 @@ Layer = namedtuple("Layer", "name N IC IH IW OC FH FW stride padding")
 # Canonical conv-layer parameters of the benchmark configurations.  "cfg4a" is
 # the deconvolution-layer upsampler (16x16x256 -> 32x32x128, 4x4, s2, p1)
 # written from the convolution side: its forward pass is the deconvolution
-# operator, its input gradient the convolution operator.
+# operator, its input gradient the convolution operator.  Its He-normal filter
+# is drawn like every other layer's, with the fan-in of the convolution side:
+# std = sqrt(2 / (FH*FW*IC)) with IC = 128 (the 32x32 side's channels), not the
+# 256 channels that feed the layer when it is used as an upsampler.  The choice
+# only scales W; timings and parity bars do not depend on it.
 LAYERS = {
     "cfg0": Layer("cfg0", 2, 4, 8, 8, 4, 3, 3, 1, 1),
     "cfg1": Layer("cfg1", 128, 64, 32, 32, 64, 3, 3, 1, 1),

@@ -38,10 +38,10 @@ def test_library_exports_every_declared_symbol(cks):
 
 
 def test_probe_library_exports_its_header(cks):
-    """The benchmark's measurement probes (include/cks_probe.h -> libcks_probe.so)."""
+    """The benchmark's measurement probes (bench_probe/cks_probe.h -> bench_probe/libcks_probe.so)."""
     from paper_2306_15951_amd import build
 
-    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "cks_probe.h")).read(), flags=re.S)
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "bench_probe", "cks_probe.h")).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(cks_probe_[a-z0-9_]+)\s*\(", text)))
     assert len(names) == 3
     if not os.path.exists(build.PROBE_LIB):

@@ -475,6 +475,38 @@ def test_presplit_mode(cks, oracle, geo):
             assert_close(dX.cpu().numpy(), want, bound, L.name + " normal")
 
 
+# Plain convolution, KS-deconv (Algorithm 2) and Sk-dilated (Algorithm 3) -- trimming off, kernel split and
+# leaping access kept -- as the ablation of bench.py runs them: the same entry points on tensors whose zero
+# border is written out.  Must equal the oracle like the trimmed operators do.
+UNTRIMMED = [
+    ("untrimmed_s1", 40, 36, 7, 6, 64, 3, 3, 1, 1),
+    ("untrimmed_s2_4x4", 33, 24, 10, 9, 32, 4, 4, 2, 1),
+    ("untrimmed_s3_pad", 20, 8, 11, 13, 12, 5, 4, 3, 2),
+    ("untrimmed_s2_remainder_pad0", 16, 12, 8, 9, 20, 3, 3, 2, 0),
+    ("untrimmed_pad_ge_filter", 12, 4, 5, 6, 8, 2, 2, 1, 3),
+    ("untrimmed_per_axis", 17, 20, 9, 12, 32, 3, 5, (2, 1), (1, 2)),
+]
+
+
+@pytest.mark.parametrize("geo", UNTRIMMED, ids=[g[0] for g in UNTRIMMED])
+def test_untrimmed_algorithms_through_the_same_kernels(cks, oracle, geo):
+    import torch
+    from paper_2306_15951_amd import synth, untrimmed
+
+    L = synth.Layer(*geo)
+    print("geometry", geo, flush=True)
+    X, W, dY = synth.make_inputs(L, "int", 77)
+    Y, dX, dW = nan_like(dY.shape), nan_like(X.shape), nan_like(W.shape)
+    for call in (untrimmed.prepare_conv2d_fwd(cks, dev(X), dev(W), Y, L.stride, L.padding),
+                 untrimmed.prepare_deconv2d(cks, dev(dY), dev(W), dX, L.stride, L.padding),
+                 untrimmed.prepare_dilated_conv2d_wgrad(cks, dev(X), dev(dY), dW, L.stride, L.padding)):
+        call()
+    torch.cuda.synchronize()
+    want = oracle_three(oracle, L, X, W, dY)
+    for got, w, nm in zip((Y, dX, dW), want, ("conv", "KS-deconv", "Sk-dilated")):
+        assert_exact(got.cpu().numpy(), w, "%s untrimmed %s" % (L.name, nm))
+
+
 GUARD = [
     ("guards", 37, 8, 7, 9, 12, 3, 3, 2, 1),
     ("guards_stem", 5, 3, 23, 26, 64, 7, 7, 2, 3),
