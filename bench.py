@@ -457,11 +457,15 @@ def main():
         configs[name] = r
         if name == a.config:
             head = (B.L, B.host, B.useful_flops)
-            if not a.no_probe:
-                k = r["roofline"]["kernel"]
-                fn = B.fwd if k == r["operators"]["conv2d_fwd"]["kernels"][0] else (
-                    B.deconv if k == r["operators"]["deconv2d"]["kernels"][0] else B.k_wgrad_main)
-                r["roofline"]["clock_under_dominant_kernel"] = mfma_probe(fn)
+        if not a.no_probe:
+            # shader clock while this layer's dominant kernel runs back to back (sampled from a second stream), and the
+            # kernel's rate against the matrix peak at that clock: what is left is the kernel's, the rest the board's
+            k = r["roofline"]["kernel"]
+            fn = B.fwd if k == r["operators"]["conv2d_fwd"]["kernels"][0] else (
+                B.deconv if k == r["operators"]["deconv2d"]["kernels"][0] else B.k_wgrad_main)
+            clk = mfma_probe(fn)
+            r["roofline"]["clock_under_dominant_kernel"] = clk
+            r["roofline"]["frac_of_peak_at_that_clock"] = r["roofline"]["frac"] * 2.4 / clk["shader_clock_ghz"]
         del B
         torch.cuda.empty_cache()
     H = configs[a.config]
