@@ -278,6 +278,31 @@ def test_paper_worked_example(oracle):
     assert np.array_equal(dW0, oracle.wgrad(X, dY, FH, FW, s, p)) and np.array_equal(dW1, dW0)
 
 
+def test_literal_upper_bound_of_algorithm_2b_contradicts_the_worked_example():
+    """Algorithm 2B as printed bounds the trimmed sub-kernel range above by the outer padding oph = extent - 1.
+    Counted that way the worked example (4x4 map, 3x3 filter, stride 2, padding 1) costs 8 operations; the
+    paper prints 50, which is what the sub-kernel extent as the bound gives."""
+    from oracle import algorithms as alg
+
+    gold = json.load(open(os.path.join(GOLDEN, "worked_example.json")))
+    g = gold["geometry"]
+    I, F, s, p = g["IH"], g["FH"], g["stride"], g["padding"]
+    O = (I + 2 * p - F) // s + 1
+
+    def taps_per_axis(literal):
+        total = 0
+        for i in range(I):
+            q, y = divmod(i + p, s)
+            ext = alg.subkernel_extent(F, y, s)
+            start = q - (ext - 1)
+            lo, hi = max(-start, 0), min(O - start, ext - 1 if literal else ext)
+            total += max(hi - lo, 0)
+        return total
+
+    assert 2 * taps_per_axis(False) ** 2 == gold["trimmed_flops"] == 50
+    assert 2 * taps_per_axis(True) ** 2 == 8
+
+
 def test_appendix_algorithms_reach_the_textbook_result(oracle):
     """Algorithms 1, 2+2B, 3+3B (with the readings listed in oracle/algorithms.py)
     against the explicit-zero operators, exactly, over the geometry sweep; all
