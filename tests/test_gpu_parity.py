@@ -636,6 +636,25 @@ def test_stem_deconv_is_reproducible_bit_for_bit(cks):
     assert np.isfinite(outs[0]).all()
 
 
+def test_deconv_without_workspace_where_none_is_used(cks, oracle):
+    """A call whose sub-kernels are read from the filter in place (OC a multiple of 32, C of 4, aligned
+    tensors) uses no workspace and accepts none; a call that needs Stage 1 is refused without one."""
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer("inplace_no_ws", 70, 36, 11, 12, 96, 3, 3, 2, 1)
+    X, W, dY = synth.make_inputs(L, "int", 8)
+    dX = nan_like(X.shape)
+    cks.cks_deconv2d(dev(dY), dev(W), dX, L.stride, L.padding, None)
+    torch.cuda.synchronize()
+    assert_exact(dX.cpu().numpy(), oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding), "in place, no workspace")
+    L2 = synth.Layer("split_needs_ws", 17, 5, 9, 10, 7, 3, 2, 2, 0)
+    X2, W2, dY2 = synth.make_inputs(L2, "int", 8)
+    with pytest.raises(cks.CksError) as e:
+        cks.cks_deconv2d(dev(dY2), dev(W2), nan_like(X2.shape), L2.stride, L2.padding, None)
+    assert e.value.status == cks.CKS_ERR_WORKSPACE
+
+
 def test_errors_on_device(cks):
     import torch
 
