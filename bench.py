@@ -10,7 +10,8 @@ default run times every benchmark layer (cfg1 ... cfg4b) and prints ONE JSON lin
   configs               per layer: step and per-operator ms (median and min of the repeats), useful
                         TFLOP/s, % of the fp32 matrix peak, the kernels each call launches, the
                         main kernels' own launch times, the input gradient with the filter split
-                        beforehand (Section V.A, pack excluded / included), and that layer's roofline
+                        beforehand and the forward pass on the filter transposed beforehand (Section V.A /
+                        IV.A, pack excluded / included), and that layer's roofline
   min_pct_fp32_mfma_peak the lowest per-operator figure over all layers, with the layer and operator
   roofline              the headline layer's dominant kernel against 157.3 TFLOP/s
   cpu_baseline          the CPU oracle on a bounded sample of the headline layer
@@ -64,6 +65,7 @@ class LayerBench:
         s = L.stride
         self.Cs = torch.empty((s, s, L.IC, -(-L.FH // s), -(-L.FW // s), L.OC), device=d)
         self.part = torch.empty((self.gz, L.OC, L.FH, L.FW, L.IC), device=d)
+        self.Wtt = torch.empty((L.FH, L.FW, L.IC, L.OC), device=d)
         self.useful_flops = 2 * cks.cks_useful_macs(*self.g)
 
     def plan(self, op):
@@ -91,6 +93,12 @@ class LayerBench:
 
     def k_deconv_presplit(self):
         self.cks.cks_deconv2d_presplit(self.dY, self.Cs, self.dX, self.L.FH, self.L.FW, self.L.stride, self.L.padding)
+
+    def k_transpose(self):
+        self.cks.cks_filter_transpose(self.W, self.Wtt)
+
+    def k_fwd_transposed(self):
+        self.cks.cks_conv2d_fwd_transposed(self.X, self.Wtt, self.Y, self.L.stride, self.L.padding)
 
     def k_wgrad_main(self):
         self.cks.cks_dilated_conv2d_wgrad_partials(self.X, self.dY, self.part, self.L.FH, self.L.FW,
@@ -280,6 +288,24 @@ def bench_layer(L, steps, warmup, repeats, settle_ms=SETTLE_MS):
         "pct_fp32_mfma_peak_pack_excluded": pct(B.useful_flops / pre_ms / 1e9),
         "pct_fp32_mfma_peak_pack_included": pct(B.useful_flops / (pre_ms + split_ms) / 1e9),
     }
+    # ... and the forward pass on the transposed filter (Section IV.A: the filter is transposed first when the
+    # input is large); the kernel exists for whole 32-channel chunks of C only
+    B.k_transpose()
+    tr_ms = statistics.median(B.time_ms(B.k_transpose, steps, warmup, repeats))
+    try:
+        B.k_fwd_transposed()
+        ft_ms = statistics.median(B.time_ms(B.k_fwd_transposed, steps, warmup, repeats))
+        out["conv2d_fwd_filter_transposed_beforehand"] = {
+            "filter_transpose_ms": tr_ms, "conv2d_fwd_transposed_ms": ft_ms, "kernels": B.plan(cks.CKS_OP_CONV2D_FWD_TRANSPOSED),
+            "pct_fp32_mfma_peak_pack_excluded": pct(B.useful_flops / ft_ms / 1e9),
+            "pct_fp32_mfma_peak_pack_included": pct(B.useful_flops / (ft_ms + tr_ms) / 1e9),
+            "speedup_over_conv2d_fwd_pack_excluded": ops["conv2d_fwd"]["ms_median"] / ft_ms,
+        }
+    except cks.CksError as e:
+        if e.status != cks.CKS_ERR_UNSUPPORTED:
+            raise
+        out["conv2d_fwd_filter_transposed_beforehand"] = {"filter_transpose_ms": tr_ms, "conv2d_fwd_transposed_ms": None,
+                                                          "note": "no kernel for this geometry (C is not a multiple of 32)"}
     dom = max(mains, key=mains.get)
     achieved = B.useful_flops / mains[dom] / 1e9
     out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",

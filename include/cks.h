@@ -53,7 +53,8 @@ typedef enum {
                                  than the padded input, or a tensor of 2^31 or more elements */
     CKS_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than the *_workspace() size */
     CKS_ERR_HIP = -4,         /* a HIP runtime call failed; see cks_last_hip_error() */
-    CKS_ERR_UNSUPPORTED = -5, /* reserved: valid geometry without an implementation */
+    CKS_ERR_UNSUPPORTED = -5, /* valid geometry that this entry point has no kernel for
+                                 (cks_conv2d_fwd_transposed; unknown op of cks_plan_hw) */
     CKS_ERR_SCRATCH = -6      /* cks_dilated_conv2d_wgrad_noalloc_hw: the call needs more than
                                  CKS_STATIC_SCRATCH_BYTES of scratch memory */
 } cks_status;
@@ -203,6 +204,22 @@ int cks_deconv2d_presplit_hw(const float *dY, const float *Cs, float *dX,
  * Wt[OC][FH][FW][C] -> Wout[FH][FW][C][OC]. */
 int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, int FW, void *stream);
 
+/* ConvV2 (Algorithm 1) on the transposed filter, the arrangement Section IV.A
+ * describes for large inputs: cks_filter_transpose once (a temporary the caller
+ * owns), then this call per step.  X [N,H,W,C] in, Wtt [FH,FW,C,OC] in (as
+ * written by cks_filter_transpose), Y [N,OH,OW,OC] out; the same result as
+ * cks_conv2d_fwd up to the order of the fp32 sums.  No workspace.  The kernel
+ * stages 32-channel chunks of the filter as they lie, so it exists only for
+ * C a multiple of 32, OC a multiple of 4 and 16-byte aligned X, Wtt: any other
+ * call returns CKS_ERR_UNSUPPORTED with nothing enqueued (cks_conv2d_fwd, which
+ * reads the filter in its given layout, serves every geometry). */
+int cks_conv2d_fwd_transposed(const float *X, const float *Wtt, float *Y,
+                              int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                              void *stream);
+int cks_conv2d_fwd_transposed_hw(const float *X, const float *Wtt, float *Y,
+                                 int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                 void *stream);
+
 /* Number of segments the contraction axis of cks_dilated_conv2d_wgrad is split
  * into for this geometry (the paper's G_Z); 0 on bad geometry. */
 int cks_dilated_conv2d_wgrad_segments(int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding);
@@ -236,7 +253,8 @@ int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segment
  * 16-byte aligned.  CKS_OP_REDUCE_PARTIALS is planned for elems = OC*FH*FW*C
  * and the geometry's own number of segments.  Returns CKS_ERR_SHAPE on bad
  * geometry, CKS_ERR_NULL without a buffer, CKS_ERR_WORKSPACE if the text did
- * not fit, CKS_ERR_UNSUPPORTED for an unknown op. */
+ * not fit, CKS_ERR_UNSUPPORTED for an unknown op (or what the entry point itself
+ * would answer). */
 typedef enum {
     CKS_OP_CONV2D_FWD = 0,
     CKS_OP_DECONV2D = 1,
@@ -245,7 +263,8 @@ typedef enum {
     CKS_OP_DECONV2D_PRESPLIT = 4,
     CKS_OP_FILTER_TRANSPOSE = 5,
     CKS_OP_WGRAD_PARTIALS = 6,
-    CKS_OP_REDUCE_PARTIALS = 7
+    CKS_OP_REDUCE_PARTIALS = 7,
+    CKS_OP_CONV2D_FWD_TRANSPOSED = 8
 } cks_op;
 int cks_plan_hw(int op, int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                 unsigned only_4byte_aligned, char *text, size_t text_bytes);

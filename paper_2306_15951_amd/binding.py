@@ -17,7 +17,7 @@ _lib = None
 CKS_OK, CKS_ERR_NULL, CKS_ERR_SHAPE, CKS_ERR_WORKSPACE, CKS_ERR_HIP, CKS_ERR_UNSUPPORTED, CKS_ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6
 CKS_STATIC_SCRATCH_BYTES = 32 << 20
 (CKS_OP_CONV2D_FWD, CKS_OP_DECONV2D, CKS_OP_DILATED_CONV2D_WGRAD, CKS_OP_KERNEL_SPLIT, CKS_OP_DECONV2D_PRESPLIT,
- CKS_OP_FILTER_TRANSPOSE, CKS_OP_WGRAD_PARTIALS, CKS_OP_REDUCE_PARTIALS) = range(8)
+ CKS_OP_FILTER_TRANSPOSE, CKS_OP_WGRAD_PARTIALS, CKS_OP_REDUCE_PARTIALS, CKS_OP_CONV2D_FWD_TRANSPOSED) = range(9)
 
 _GEO = [ctypes.c_int] * 9
 _GEO_HW = [ctypes.c_int] * 11   # N, C, H, W, OC, FH, FW, sh, sw, ph, pw
@@ -52,6 +52,8 @@ _PROTOTYPES = {
     "cks_dilated_conv2d_wgrad_segments_hw": (_GEO_HW, ctypes.c_int),
     "cks_dilated_conv2d_wgrad_partials_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
     "cks_dilated_conv2d_wgrad_noalloc_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_conv2d_fwd_transposed": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p], ctypes.c_int),
+    "cks_conv2d_fwd_transposed_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
     "cks_plan_hw": ([ctypes.c_int] + _GEO_HW + [ctypes.c_uint, ctypes.c_char_p, ctypes.c_size_t], ctypes.c_int),
     "cks_strerror": ([ctypes.c_int], ctypes.c_char_p),
     "cks_last_hip_error": ([], ctypes.c_int),
@@ -344,3 +346,22 @@ def cks_dilated_conv2d_wgrad_noalloc_hw(X, dY, dW, stride, padding):
                                                      N, C, H, W, OC, FH, FW, *stride, *padding, _stream()),
            "cks_dilated_conv2d_wgrad_noalloc_hw")
     return dW
+
+
+def cks_conv2d_fwd_transposed(X, Wtt, Y, stride, padding):
+    """Y[N,OH,OW,OC] <- ConvV2(X[N,H,W,C], Wtt[FH,FW,C,OC]), the filter as cks_filter_transpose writes it."""
+    N, H, W, C = X.shape
+    FH, FW, _, OC = Wtt.shape
+    OH, OW = cks_out_dims(H, W, FH, FW, stride, padding)
+    _check(lib().cks_conv2d_fwd_transposed(_ptr(X, "X"), _ptr(Wtt, "Wtt", (FH, FW, C, OC)), _ptr(Y, "Y", (N, OH, OW, OC)),
+                                           N, C, H, W, OC, FH, FW, stride, padding, _stream()), "cks_conv2d_fwd_transposed")
+    return Y
+
+
+def cks_conv2d_fwd_transposed_hw(X, Wtt, Y, stride, padding):
+    N, H, W, C = X.shape
+    FH, FW, _, OC = Wtt.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    _check(lib().cks_conv2d_fwd_transposed_hw(_ptr(X, "X"), _ptr(Wtt, "Wtt", (FH, FW, C, OC)), _ptr(Y, "Y", (N, OH, OW, OC)),
+                                              N, C, H, W, OC, FH, FW, *stride, *padding, _stream()), "cks_conv2d_fwd_transposed_hw")
+    return Y

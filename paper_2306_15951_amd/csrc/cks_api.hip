@@ -215,7 +215,7 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     // lose in locality did not show).  Not for KS-deconv with several classes: its class-major list wants
     // neighbouring positions on one die (bands of 16 or 64 workgroups instead of 32 cost 12 points on the
     // stride-2 benchmark layer).
-    P.pairFlip = OP == OP_FWD || (P.sh == 1 && P.sw == 1);
+    P.pairFlip = op_is_fwd(OP) || (P.sh == 1 && P.sw == 1);
     long long g = items / (4 * kXcds);
     g = g < 1 ? 1 : (g > P.itemsW ? P.itemsW : g);
     long long bandBlocks = P.pairFlip && items < 16 * kXcds ? 2 : g * P.mTiles * P.nTiles;
@@ -240,24 +240,24 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     P.pmodsW = P.pw % P.sw;
     {
         // output rows of a tile are one image apart
-        const long long rowO = OP == OP_FWD ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;
+        const long long rowO = op_is_fwd(OP) ? (long long)P.OH * P.OW * P.OC : (long long)P.IH * P.IW * P.IC;
         P.bufStore = rowO * BM * 4 < (1LL << 31) && !tune("CKS_TUNE_NO_BUFFER_STORES");
     }
     const size_t lds = rowrun_lds_bytes<BM, BN>();
     // Fast loads need: 16-byte vectors, every run a whole number of 32-float
     // chunks (the run is a multiple of the contracted channel count), and the
     // tile's rows within 2 GiB of its first one.
-    const long long kch = OP == OP_FWD ? P.IC : P.OC;
-    const long long rowA = OP == OP_FWD ? (long long)P.IH * P.IW * P.IC : (long long)P.OH * P.OW * P.OC;
-    const long long rowB = OP == OP_FWD ? (long long)P.FH * P.FW * P.IC : (long long)P.CHp * P.CWp * P.OC;
+    const long long kch = op_is_fwd(OP) ? P.IC : P.OC;
+    const long long rowA = op_is_fwd(OP) ? (long long)P.IH * P.IW * P.IC : (long long)P.OH * P.OW * P.OC;
+    const long long rowB = op_is_fwd(OP) ? (long long)P.FH * P.FW * P.IC : (long long)P.CHp * P.CWp * P.OC;
     // the default tiles also exist with their chunks loaded straight into LDS (same conditions as the fast loads)
     constexpr bool kHasDma = (BM == 64 && BN == 64 && WM == 2 && WN == 2) ||
-                             (BM == 128 && BN == 32 && WM == 4 && WN == 1 && OP != OP_DECONV_W);   // (the in-place filter tile is laid out for 64 columns)
+                             (BM == 128 && BN == 32 && WM == 4 && WN == 1 && !op_b_k_major(OP));   // (the K-major filter tile is laid out for 64 columns)
     // (kernels that only a tuning build can select are not instantiated otherwise)
     const bool dma = kHasDma && !tune("CKS_TUNE_NO_LDS_DIRECT");
     constexpr bool kAlwaysDma = kHasDma && !kTuning;
-    if constexpr (OP == OP_DECONV_W) {
-        // the caller has checked deconv_in_place_ok: only the fast-load variants exist
+    if constexpr (op_b_k_major(OP)) {
+        // the caller has checked deconv_in_place_ok / fwd_transposed_ok: only the fast-load variants exist
         if constexpr (kHasDma)
             if (dma) return launch(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
         if constexpr (!kAlwaysDma)
@@ -316,7 +316,7 @@ RowRunParams rowrun_params(const Geo &g, const float *A, const float *B, float *
     P.FH = g.FH; P.FW = g.FW; P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw;
     P.CHp = (g.FH + g.sh - 1) / g.sh;
     P.CWp = (g.FW + g.sw - 1) / g.sw;
-    if (OP == OP_FWD) {
+    if (op_is_fwd(OP)) {
         P.itemsH = g.OH; P.itemsW = g.OW;
         P.rotH = ((g.ph + g.sh - 1) / g.sh) % g.OH;       // output rows whose window starts in the padding
         P.rotW = ((g.pw + g.sw - 1) / g.sw) % g.OW;
@@ -705,6 +705,22 @@ int conv_fwd(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_
     return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), N, OC, vec, st);
 }
 
+// ConvV2 on the transposed filter Wtt[FH][FW][C][OC] (Section IV.A, last paragraph).  For one tap the filter
+// is then a K x N matrix (ic x oc) with N contiguous; its 32 x 64 chunks go to LDS as they lie.  Needs whole
+// 32-channel chunks of C, 16-byte vectors, tile rows of X within 2 GiB of the first, the filter below 2 GiB.
+bool fwd_transposed_ok(const Geo &g, const float *X, const float *Wtt)
+{
+    const long long rowA = (long long)g.H * g.W * g.C, w = (long long)g.OC * g.FH * g.FW * g.C;
+    return g.C % 32 == 0 && g.OC % 4 == 0 && aligned16(X) && aligned16(Wtt) && rowA * 129 * 4 < (1LL << 31) && w * 4 < (1LL << 31);
+}
+
+int conv_fwd_transposed(const Geo &g, const float *X, const float *Wtt, float *Y, hipStream_t st)
+{
+    if (!X || !Wtt || !Y) return CKS_ERR_NULL;
+    if (!fwd_transposed_ok(g, X, Wtt)) return CKS_ERR_UNSUPPORTED;
+    return dispatch_rowrun<OP_FWD_T>(rowrun_params<OP_FWD_T>(g, X, Wtt, Y), g.N, g.OC, true, st);
+}
+
 int kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int sh, int sw, hipStream_t st)
 {
     if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || sh < 1 || sw < 1 || sh > (1 << 20) || sw > (1 << 20)) return CKS_ERR_SHAPE;
@@ -1011,6 +1027,23 @@ int cks_filter_transpose(const float *Wt, float *Wout, int C, int OC, int FH, in
     return launch_pack<PACK_TRANSPOSE>(Wt, Wout, C, OC, FH, FW, 1, 1, (hipStream_t)stream);
 }
 
+int cks_conv2d_fwd_transposed_hw(const float *X, const float *Wtt, float *Y,
+                                 int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                 void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return conv_fwd_transposed(g, X, Wtt, Y, (hipStream_t)stream);
+}
+
+int cks_conv2d_fwd_transposed(const float *X, const float *Wtt, float *Y,
+                              int N, int C, int H, int W, int OC, int FH, int FW, int stride, int padding,
+                              void *stream)
+{
+    return cks_conv2d_fwd_transposed_hw(X, Wtt, Y, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, stream);
+}
+
 int cks_deconv2d_presplit_hw(const float *dY, const float *Cs, float *dX,
                              int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                              void *stream)
@@ -1098,6 +1131,7 @@ int cks_plan_hw(int op, int N, int C, int H, int W, int OC, int FH, int FW, int 
         case CKS_OP_FILTER_TRANSPOSE: rc = cks_filter_transpose(a, b, C, OC, FH, FW, nullptr); break;
         case CKS_OP_WGRAD_PARTIALS: rc = wgrad_partials(g, a, b, c, nullptr); break;
         case CKS_OP_REDUCE_PARTIALS: rc = cks_reduce_partials(a, b, (int64_t)OC * FH * FW * C, plan_wgrad(g).GZ, nullptr); break;
+        case CKS_OP_CONV2D_FWD_TRANSPOSED: rc = conv_fwd_transposed(g, a, b, c, nullptr); break;
         default: rc = CKS_ERR_UNSUPPORTED; break;
     }
     g_plan = nullptr;
@@ -1113,7 +1147,7 @@ const char *cks_strerror(int status)
         case CKS_ERR_SHAPE: return "invalid or too large tensor geometry";
         case CKS_ERR_WORKSPACE: return "workspace missing or too small";
         case CKS_ERR_HIP: return "HIP runtime error (see cks_last_hip_error)";
-        case CKS_ERR_UNSUPPORTED: return "geometry not supported";
+        case CKS_ERR_UNSUPPORTED: return "this entry point has no kernel for the geometry or pointer alignment";
         case CKS_ERR_SCRATCH: return "the call needs more scratch memory than the library's static buffer holds";
         default: return "unknown status";
     }

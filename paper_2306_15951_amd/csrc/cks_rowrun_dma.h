@@ -15,7 +15,8 @@
 //     c (0..7) of row r is stored at piece position c ^ ((r >> 1) & 7).  The 16 lanes that the LDS serves
 //     together read one piece each from 16 consecutive rows: 8 even and 8 odd rows, which differ in bit 5
 //     of the bank number and, within each parity, in all 8 piece positions.
-//   K-major operand (B of the KS-deconv that reads the filter in place): tile [32 k][BN floats], piece c of
+//   K-major operand (B of the KS-deconv that reads the filter in place and of ConvV2 on the transposed
+//     filter): tile [32 k][BN floats], piece c of
 //     k-row k is stored at piece position c ^ (8 * ((k >> 2) & 1)) -- the two lane halves of a fragment
 //     read rows k and k + 4 at the same column and now fall into different bank halves.
 // A lane simply fetches the global piece that belongs at its fixed LDS position.
@@ -40,7 +41,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
     constexpr int KC = 32;
     constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
     constexpr int IA = BM / 32, IB = BN / 32;      // LDS-direct loads per wave and chunk (1 KB each)
-    constexpr bool BK = OP == OP_DECONV_W;
+    constexpr bool BK = op_b_k_major(OP);
     constexpr int ABUF = BM * KC * 4, BBUF = BN * KC * 4;   // bytes per buffer
     static_assert(WAVES_M * WAVES_N == 4 && TM >= 1 && TN >= 1 && TM <= 2 && TN <= 2, "4 waves, up to 2 x 2 blocks each");
     static_assert(!BK || (BN == 64 && TN == 1), "the K-major tile is laid out for 64 columns, one block per wave");
@@ -56,7 +57,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
     int ph = fdiv(item, P.dItemsW), pw = item - ph * P.itemsW;
     ph += P.rotH; if (ph >= P.itemsH) ph -= P.itemsH;
     pw += P.rotW; if (pw >= P.itemsW) pw -= P.itemsW;
-    if (OP != OP_FWD) {
+    if (!op_is_fwd(OP)) {
         ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH);
         pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW);
     }
@@ -109,9 +110,9 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(P.A + (long)min(m0, P.N - 1) * R.strideA + R.a0), 0, -1, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsB =
-        BK ? __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + n0), 0, (int)(((long)P.OC * R.strideB - n0) * 4), 0x00020000)
+        BK ? __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + n0), 0, (int)(((long)P.OC * P.FH * P.FW * P.IC - n0) * 4), 0x00020000)
            : __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + (long)min(n0, R.NC - 1) * R.strideB + R.b0), 0, -1, 0x00020000);
-    const int ocChunks = P.OC / KC;   // BK: chunks per cw
+    const int ocChunks = (op_is_fwd(OP) ? P.IC : P.OC) / KC;   // BK: chunks per tap of a run (the contracted channels)
 
     int run = 0, ck = 0, cwi = 0, occ = 0;   // chunk being loaded (BK: output channels 32*occ.. of sub-kernel column cw_s + cwi)
     auto next_chunk = [&]() {

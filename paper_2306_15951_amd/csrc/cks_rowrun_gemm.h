@@ -30,7 +30,11 @@
 namespace cks {
 
 // OP_DECONV_W: KS-deconv Stage 2&3 that takes its sub-kernels straight from the OHWI filter (see below)
-enum { OP_FWD = 0, OP_DECONV = 1, OP_DECONV_W = 2 };
+// OP_FWD_T:    ConvV2 on the transposed filter Wt[FH][FW][IC][OC] of Section IV.A (last paragraph): for one tap
+//              the filter is a K x N matrix (ic x oc) with N contiguous, staged K-major like OP_DECONV_W's
+enum { OP_FWD = 0, OP_DECONV = 1, OP_DECONV_W = 2, OP_FWD_T = 3 };
+constexpr bool op_is_fwd(int op) { return op == OP_FWD || op == OP_FWD_T; }        // positions are those of Y
+constexpr bool op_b_k_major(int op) { return op == OP_DECONV_W || op == OP_FWD_T; }  // B chunk = 32 k-rows x BN columns
 
 struct RowRunParams {
     const float *A;   // X (fwd) or dY (deconv)
@@ -88,7 +92,7 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 {
     RunSet R;
     R.bCw = 0;
-    if (OP == OP_FWD) {
+    if (op_is_fwd(OP)) {
         // Algorithm 1: trim [fh_s,fh_e) x [fw_s,fw_e) of the filter at (oh,ow).
         const int oh = ph, ow = pw;
         int ih_s = oh * P.sh - P.ph, iw_s = ow * P.sw - P.pw;
@@ -99,9 +103,18 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         R.a0 = ((long)(ih_s + fh_s) * P.IW + (iw_s + fw_s)) * P.IC;
         R.aRun = (long)P.IW * P.IC;
         R.strideA = (long)P.IH * P.IW * P.IC;
-        R.b0 = ((long)fh_s * P.FW + fw_s) * P.IC;
-        R.bRun = (long)P.FW * P.IC;
-        R.strideB = (long)P.FH * P.FW * P.IC;
+        if (OP == OP_FWD_T) {
+            // run r is filter row fh_s + r of Wt[FH][FW][IC][OC]; within it the taps fw_s.. follow each other
+            // IC*OC floats apart, and consecutive k (input channels) are OC floats apart
+            R.strideB = P.OC;
+            R.b0 = ((long)fh_s * P.FW + fw_s) * P.IC * P.OC;
+            R.bRun = (long)P.FW * P.IC * P.OC;
+            R.bCw = (long)P.IC * P.OC;
+        } else {
+            R.b0 = ((long)fh_s * P.FW + fw_s) * P.IC;
+            R.bRun = (long)P.FW * P.IC;
+            R.strideB = (long)P.FH * P.FW * P.IC;
+        }
         R.o0 = ((long)oh * P.OW + ow) * P.OC;
         R.strideO = (long)P.OH * P.OW * P.OC;
         R.NC = P.OC;
@@ -233,8 +246,9 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     constexpr int TM = BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
     constexpr int PA = BM / 32, PB = BN / 32;
     static_assert(WAVES_M * WAVES_N == 4 && TM >= 1 && TN >= 1, "4 waves per workgroup");
-    // OP_DECONV_W: B chunk = 32 output channels (K) x BN input channels, staged K-major
-    constexpr bool BK = OP == OP_DECONV_W;
+    // OP_DECONV_W: B chunk = 32 output channels (K) x BN input channels, staged K-major (OP_FWD_T: 32 input
+    // channels x BN output channels)
+    constexpr bool BK = op_b_k_major(OP);
     constexpr int LDB = BN + 4, TPR = BN / 4, RPP = kThreads / TPR;   // floats per k-row, threads / rows per staging pass
     static_assert(!BK || LOAD == LOAD_FAST, "the filter is read in place only by the fast-load variant");
     static_assert(!BK || 2 * KC * LDB <= 2 * BN * LDK, "the K-major B buffers fit the LDS of the row-major ones");
@@ -250,7 +264,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     int ph = fdiv(item, P.dItemsW), pw = item - ph * P.itemsW;
     ph += P.rotH; if (ph >= P.itemsH) ph -= P.itemsH;   // rotH < itemsH
     pw += P.rotW; if (pw >= P.itemsW) pw -= P.itemsW;
-    if (OP != OP_FWD) {
+    if (!op_is_fwd(OP)) {
         ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH);
         pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW);
     }
@@ -301,10 +315,10 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     // BK: the filter from column n0 on, as a buffer of its true size
     const __amdgpu_buffer_rsrc_t rsB =
         BK ? __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + n0), 0,
-                                               (int)(((long)P.OC * R.strideB - n0) * 4), 0x00020000)
+                                               (int)(((long)P.OC * P.FH * P.FW * P.IC - n0) * 4), 0x00020000)
            : __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + (long)min(n0, R.NC - 1) * R.strideB + R.b0), 0, -1,
                                                0x00020000);
-    const int ocChunks = P.OC / KC;   // BK: chunks per cw
+    const int ocChunks = (op_is_fwd(OP) ? P.IC : P.OC) / KC;   // BK: chunks per tap of a run (the contracted channels)
 
     // One register set: the loads of chunk t+1 are issued before chunk t is
     // multiplied out of LDS and stored to the other LDS buffer after it.  (A
@@ -312,7 +326,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     struct Stage { float4 a[PA], b[PB]; };
     Stage S0;
     // `live` false: nothing is read; the masked modes then stage zeros.
-    int cwi = 0, occ = 0;   // BK: the chunk being loaded is output channels 32*occ.. of sub-kernel column cw_s + cwi
+    int cwi = 0, occ = 0;   // BK: the chunk being loaded is contracted channels 32*occ.. of the run's tap number cwi
     auto gload = [&](Stage &S, int run, int ck, bool live) {
         if (LOAD == LOAD_FAST) {
             if (!live) return;   // uniform

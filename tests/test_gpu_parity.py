@@ -388,7 +388,7 @@ def test_tensors_beyond_2GiB_sampled(cks, oracle):
 def test_full_size_cfg1_every_element(cks, oracle):
     """One benchmark layer compared in full, not sampled: all three operators, and the input gradient
     once more in the mode with the filter operations done before the loop (Stage 1, then Stage 2&3 on
-    the split filter)."""
+    the split filter), and the forward pass once more on the transposed filter."""
     import torch
     from paper_2306_15951_amd import synth
 
@@ -403,8 +403,13 @@ def test_full_size_cfg1_every_element(cks, oracle):
     dX2 = nan_like(X.shape)
     cks.cks_kernel_split(dev(W), Cs, 1)
     cks.cks_deconv2d_presplit(dev(dY), Cs, dX2, L.FH, L.FW, L.stride, L.padding)
+    Wtt = nan_like((L.FH, L.FW, L.IC, L.OC))
+    Y2 = nan_like(dY.shape)
+    cks.cks_filter_transpose(dev(W), Wtt)
+    cks.cks_conv2d_fwd_transposed(dev(X), Wtt, Y2, L.stride, L.padding)
     torch.cuda.synchronize()
     assert_exact(dX2.cpu().numpy(), want_dX, "cfg1 deconv on the pre-split filter, full")
+    assert_exact(Y2.cpu().numpy(), oracle.conv_fwd(X, W, L.stride, L.padding), "cfg1 fwd on the transposed filter, full")
 
 
 STAGE1 = [(40, 3, 3, 36, 2), (7, 7, 7, 3, 2), (33, 4, 4, 65, 2), (8, 5, 3, 12, 3), (16, 3, 3, 16, 1), (4, 1, 1, 4, 2)]   # OC, FH, FW, IC, stride
@@ -473,6 +478,60 @@ def test_presplit_mode(cks, oracle, geo):
         else:
             bound = oracle.deconv(np.abs(dY), np.abs(W), L.IH, L.IW, L.stride, L.padding)
             assert_close(dX.cpu().numpy(), want, bound, L.name + " normal")
+
+
+# ConvV2 on the transposed filter (Section IV.A: filter transposition before the convolution): 64-column tiles
+# loaded straight into LDS, narrow outputs on the 128x32 tile, ragged batch / channel tiles, strides, per-axis
+# geometry, padding beyond the filter, one tap
+FWD_TRANSPOSED = [
+    ("fwdt_s1", 70, 64, 7, 8, 100, 3, 3, 1, 1),
+    ("fwdt_s2_two_chunks", 96, 64, 11, 9, 96, 3, 3, 2, 1),
+    ("fwdt_narrow_output", 130, 32, 9, 9, 40, 3, 3, 1, 1),
+    ("fwdt_5x4_s3", 33, 32, 13, 11, 128, 5, 4, 3, 2),
+    ("fwdt_pad_ge_filter", 12, 32, 5, 6, 8, 2, 2, 1, 3),
+    ("fwdt_one_by_one", 200, 96, 5, 5, 68, 1, 1, 1, 0),
+    ("fwdt_per_axis", 64, 32, 9, 12, 64, 3, 3, (1, 2), (1, 0)),
+    ("fwdt_per_axis_narrow", 40, 64, 13, 11, 20, 4, 5, (2, 3), (1, 2)),
+]
+
+
+@pytest.mark.parametrize("geo", FWD_TRANSPOSED, ids=[g[0] for g in FWD_TRANSPOSED])
+def test_forward_on_the_transposed_filter(cks, oracle, geo):
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer(*geo)
+    print("geometry", geo, flush=True)
+    hw = isinstance(L.stride, tuple)
+    for kind in ("int", "normal"):
+        X, W, _ = synth.make_inputs(L, kind, 55)
+        Wtt = nan_like((L.FH, L.FW, L.IC, L.OC))
+        cks.cks_filter_transpose(dev(W), Wtt)
+        OH, OW = synth.out_hw(L)
+        Y = nan_like((L.N, OH, OW, L.OC))
+        if hw:
+            cks.cks_conv2d_fwd_transposed_hw(dev(X), Wtt, Y, synth.pair(L.stride), synth.pair(L.padding))
+        else:
+            cks.cks_conv2d_fwd_transposed(dev(X), Wtt, Y, L.stride, L.padding)
+        torch.cuda.synchronize()
+        want = oracle.conv_fwd(X, W, L.stride, L.padding)
+        if kind == "int":
+            assert_exact(Y.cpu().numpy(), want, L.name + " int")
+        else:
+            assert_close(Y.cpu().numpy(), want, oracle.conv_fwd(np.abs(X), np.abs(W), L.stride, L.padding), L.name + " normal")
+
+
+def test_forward_on_the_transposed_filter_says_what_it_cannot_do(cks):
+    import torch
+
+    X = torch.zeros((4, 6, 6, 36), device="cuda")          # 36 input channels: no whole 32-channel chunks
+    Wtt = torch.zeros((3, 3, 36, 8), device="cuda")
+    Y = torch.full((4, 6, 6, 8), 7.0, device="cuda")
+    with pytest.raises(cks.CksError) as e:
+        cks.cks_conv2d_fwd_transposed(X, Wtt, Y, 1, 1)
+    assert e.value.status == cks.CKS_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((Y == 7.0).all())
 
 
 # Plain convolution, KS-deconv (Algorithm 2) and Sk-dilated (Algorithm 3) -- trimming off, kernel split and
@@ -676,7 +735,7 @@ def planned_calls():
     these calls select, and fails if a kernel the library was built with is selected by none of them."""
     from paper_2306_15951_amd import synth
 
-    FWD, DECONV, WGRAD, SPLIT, PRESPLIT_OP, TRANSPOSE, PARTIALS, REDUCE = range(8)
+    FWD, DECONV, WGRAD, SPLIT, PRESPLIT_OP, TRANSPOSE, PARTIALS, REDUCE, FWD_T = range(9)
     calls = []
     three = [tuple(synth.LAYERS["cfg0"])] + MID + RANDOM + ASYM + RANDOM_ASYM + WIDE_TILE
     three += [tuple(synth.LAYERS[n]) for n in FULL] + [("beyond_2GiB", 9, 64, 1024, 1024, 16, 3, 3, 1, 1)]
@@ -684,7 +743,9 @@ def planned_calls():
         calls += [(op, geo, 0) for op in (FWD, DECONV, WGRAD)]
     for geo in GUARD:                                    # once aligned, once with every pointer one float off
         calls += [(op, geo, m) for op in (FWD, DECONV, WGRAD) for m in (0, 15)]
-    calls += [(op, tuple(synth.LAYERS["cfg1"]), 0) for op in (SPLIT, PRESPLIT_OP)]
+    calls += [(op, tuple(synth.LAYERS["cfg1"]), 0) for op in (SPLIT, PRESPLIT_OP, TRANSPOSE, FWD_T)]
+    for geo in FWD_TRANSPOSED:
+        calls += [(op, geo, 0) for op in (TRANSPOSE, FWD_T)]
     for (OC, FH, FW, IC, s) in STAGE1:
         calls += [(op, ("stage1", 1, IC, FH, FW, OC, FH, FW, s, 0), 0) for op in (SPLIT, TRANSPOSE)]
     for geo in PRESPLIT:
