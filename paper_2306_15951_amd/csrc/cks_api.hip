@@ -322,9 +322,7 @@ RowRunParams rowrun_params(const Geo &g, const float *A, const float *B, float *
         P.rotW = ((g.pw + g.sw - 1) / g.sw) % g.OW;
     } else {
         P.itemsH = g.H; P.itemsW = g.W;
-        const int th = g.FH - 1 - g.ph > 0 ? g.FH - 1 - g.ph : 0, tw = g.FW - 1 - g.pw > 0 ? g.FW - 1 - g.pw : 0;
-        P.rotH = ((th + g.sh - 1) / g.sh) % g.H;          // positions per class whose dY window starts above row 0
-        P.rotW = ((tw + g.sw - 1) / g.sw) % g.W;
+        P.rotH = 0; P.rotW = 0;   // the class-major list is rotated class by class (class_major_index)
     }
     return P;
 }

@@ -58,8 +58,8 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
     ph += P.rotH; if (ph >= P.itemsH) ph -= P.itemsH;
     pw += P.rotW; if (pw >= P.itemsW) pw -= P.itemsW;
     if (!op_is_fwd(OP)) {
-        ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH);
-        pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW);
+        ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH, P.FH, P.ph);
+        pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW, P.FW, P.pw);
     }
     const int m0 = mt * BM, n0 = nt * BN;
 

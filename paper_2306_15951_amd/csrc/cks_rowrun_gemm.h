@@ -44,10 +44,10 @@ struct RowRunParams {
     int sh, sw, ph, pw;   // stride and padding per axis (Table I: <sh sw>, <ph pw>)
     int CHp, CWp;     // ceil(FH/sh), ceil(FW/sw): padded sub-kernel extents
     // Work decomposition: one output position (of Y, resp. dX) times one tile.
-    // Positions are issued roughly most expensive first: the list starts at
+    // Positions are issued roughly most expensive first: ConvV2's list starts at
     // (rotH, rotW), the first position with an untrimmed window, and wraps
-    // around to the border; KS-deconv in addition lists the positions class by
-    // class (larger sub-kernels first).
+    // around to the border; KS-deconv lists the positions class by class (larger
+    // sub-kernels first) and does the same within each class (rotH = rotW = 0).
     int itemsH, itemsW;   // grid of positions
     int rotH, rotW;
     int mTiles, nTiles;
@@ -71,15 +71,28 @@ struct RunSet {
 
 // The a-th index of [0, I) when indices are listed class by class, class
 // y = (i + p) mod s, y = 0, 1, ...  (sub-kernel extents shrink with y, so the
-// classes with most work come first).
-__device__ inline int class_major_index(int a, int I, const FastDiv &dS, int pmods)
+// classes with most work come first).  Within a class the list starts at its first
+// index whose window over dY is not cut at the low end and wraps around to those
+// that are: every class then runs from its dearest to its cheapest positions, and
+// the list as a whole from the dearest class to the cheapest.  (Rotating the list
+// as a whole instead moves a row of the dearest class behind the cheapest one: on a
+// layer whose workgroups are all resident at once that row is dispatched last, gets
+// what is left of the issue slots and finishes last -- 7 % on the stride-2 benchmark layer.)
+__device__ inline int class_major_index(int a, int I, const FastDiv &dS, int pmods, int F, int p)
 {
     const int s = dS.d;
     for (int y = 0; y < s; ++y) {
         int i0 = y - pmods;   // first index of class y: (y - p) mod s
         if (i0 < 0) i0 += s;
         int cnt = i0 < I ? fdiv(I - 1 - i0, dS) + 1 : 0;
-        if (a < cnt) return i0 + a * s;
+        if (a < cnt) {
+            // index i0 + j s has window start q0 + j - (CH - 1): cut at the low end while j < CH - 1 - q0
+            const int CH = y < F ? fdiv(F - y + s - 1, dS) : 0, q0 = fdiv(i0 + p - y, dS);
+            const int lead = min(max(CH - 1 - q0, 0), cnt);
+            int j = a + lead;
+            if (j >= cnt) j -= cnt;
+            return i0 + j * s;
+        }
         a -= cnt;
     }
     return 0;  // not reached for 0 <= a < I
@@ -265,8 +278,8 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm(const RowRunParams P)
     ph += P.rotH; if (ph >= P.itemsH) ph -= P.itemsH;   // rotH < itemsH
     pw += P.rotW; if (pw >= P.itemsW) pw -= P.itemsW;
     if (!op_is_fwd(OP)) {
-        ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH);
-        pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW);
+        ph = class_major_index(ph, P.IH, P.dSh, P.pmodsH, P.FH, P.ph);
+        pw = class_major_index(pw, P.IW, P.dSw, P.pmodsW, P.FW, P.pw);
     }
     const int m0 = mt * BM, n0 = nt * BN;
 
