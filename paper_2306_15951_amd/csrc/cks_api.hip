@@ -216,7 +216,10 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     // neighbouring positions on one die (bands of 16 or 64 workgroups instead of 32 cost 12 points on the
     // stride-2 benchmark layer).
     P.pairFlip = op_is_fwd(OP) || (P.sh == 1 && P.sw == 1);
-    long long g = items / (4 * kXcds);
+    // (KS-deconv with several classes: two per die -- on the 16x16 stride-2 benchmark layer a band is then a whole
+    // row of positions, every compute unit still holds one tile of each class, and the layer runs 2 points faster
+    // than with half rows; smaller or larger bands put two tiles of the dearest class on one compute unit: -13 points)
+    long long g = items / ((P.pairFlip ? 4 : 2) * kXcds);
     g = g < 1 ? 1 : (g > P.itemsW ? P.itemsW : g);
     long long bandBlocks = P.pairFlip && items < 16 * kXcds ? 2 : g * P.mTiles * P.nTiles;
     if (const char *t = tune("CKS_TUNE_BAND")) { if (atoi(t) > 0) bandBlocks = atoi(t); }   // tuning experiments only
