@@ -155,3 +155,17 @@ def test_no_alloc_entry_point_checks_its_limit_on_the_host(cks):
     assert b"static" in L.cks_strerror(cks.CKS_ERR_SCRATCH)
     text = open(os.path.join(ROOT, "include", "cks.h")).read()
     assert "#define CKS_STATIC_SCRATCH_BYTES (32u << 20)" in text and cks.CKS_STATIC_SCRATCH_BYTES == 32 << 20
+
+
+def test_forward_on_the_transposed_filter_refuses_on_the_host(cks):
+    """cks_conv2d_fwd_transposed has a kernel for whole 32-channel chunks of C, OC a multiple of 4 and 16-byte
+    aligned pointers only; everything else is refused before any device call."""
+    L = cks.lib()
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    assert L.cks_conv2d_fwd_transposed(fake, fake, fake, 4, 36, 6, 6, 8, 3, 3, 1, 1, None) == cks.CKS_ERR_UNSUPPORTED   # C = 36
+    assert L.cks_conv2d_fwd_transposed(fake, fake, fake, 4, 32, 6, 6, 6, 3, 3, 1, 1, None) == cks.CKS_ERR_UNSUPPORTED   # OC = 6
+    assert L.cks_conv2d_fwd_transposed(odd, fake, fake, 4, 32, 6, 6, 8, 3, 3, 1, 1, None) == cks.CKS_ERR_UNSUPPORTED    # X off by a float
+    assert L.cks_conv2d_fwd_transposed(None, fake, fake, 4, 32, 6, 6, 8, 3, 3, 1, 1, None) == cks.CKS_ERR_NULL
+    assert L.cks_conv2d_fwd_transposed_hw(fake, fake, fake, 4, 32, 6, 6, 8, 3, 3, 0, 1, 1, 1, None) == cks.CKS_ERR_SHAPE
+    names = [k for k, _ in cks.cks_plan_hw(cks.CKS_OP_CONV2D_FWD_TRANSPOSED, 128, 64, 32, 32, 64, 3, 3, (1, 1), (1, 1))]
+    assert names == ["rowrun_gemm_dma<3, 64, 64, 2, 2>"]
