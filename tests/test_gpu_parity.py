@@ -385,6 +385,22 @@ def test_tensors_beyond_2GiB_sampled(cks, oracle):
     check_layer(cks, oracle, L, seed=9, kinds=("normal",), samples=samples)
 
 
+@pytest.mark.parametrize("name", ["cfg2", "cfg3b", "cfg4a"])
+def test_full_size_layers_every_element(cks, oracle, name):
+    """Three more benchmark layers compared in full (every output element of all three operators, integer
+    inputs, bit for bit): the stride-2 layer with its four sub-kernel classes, the 4x4-map layer whose
+    trimmed taps are 31 % of the filter, and the 4x4-filter upsampler."""
+    from paper_2306_15951_amd import synth
+
+    L = synth.LAYERS[name]
+    print("layer", L, flush=True)
+    X, W, dY = synth.make_inputs(L, "int", 6)
+    Y, dX, dW = run_three(cks, L, X, W, dY)
+    assert_exact(Y, oracle.conv_fwd(X, W, L.stride, L.padding), name + " fwd full")
+    assert_exact(dX, oracle.deconv(dY, W, L.IH, L.IW, L.stride, L.padding), name + " deconv full")
+    assert_exact(dW, oracle.wgrad(X, dY, L.FH, L.FW, L.stride, L.padding), name + " wgrad full")
+
+
 def test_full_size_cfg1_every_element(cks, oracle):
     """One benchmark layer compared in full, not sampled: all three operators, and the input gradient
     once more in the mode with the filter operations done before the loop (Stage 1, then Stage 2&3 on
