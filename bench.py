@@ -350,8 +350,12 @@ def ablation(L, steps, warmup):
 
       skip       the operator as the library runs it (ConvV2, KS-deconv-V2, Sk-dilated-V2)
       untrimmed  trimming off, kernel split / leaping access kept: plain convolution, KS-deconv
-                 (Algorithm 2), Sk-dilated (Algorithm 3) -- the same entry points on tensors whose zero
-                 border is written out (paper_2306_15951_amd/untrimmed.py)
+                 (Algorithm 2), Sk-dilated (Algorithm 3) -- the library's *_untrimmed entry points: the
+                 same kernels built without the trimming, on the same tensors; the window cells outside
+                 the data are fetched as zeros by the loads and multiplied
+      untrimmed_materialised
+                 the same three algorithms through the library's ordinary entry points, on tensors
+                 whose zero border is written out (paper_2306_15951_amd/untrimmed.py)
       dense      the textbook form that multiplies every zero: padded input; stride-inserted zeros on a
                  canvas + rotated filter at unit stride; the dilated gradient as a filter -- all through
                  cks_conv2d_fwd with padding 0
@@ -378,22 +382,27 @@ def ablation(L, steps, warmup):
     def close(a, b):
         return float((a - b).abs().max() / max(float(b.abs().max()), 1e-30))
 
-    def row(skip, untrim, dense, got_untrim, got_dense, want):
-        skip(); untrim(); dense()
+    def row(skip, untrim, mat, dense, got_untrim, got_mat, got_dense, want):
+        skip(); untrim(); mat(); dense()
         torch.cuda.synchronize()
-        d = {"max_rel_diff_untrimmed": close(got_untrim(), want()), "max_rel_diff_dense": close(got_dense(), want())}
-        d["skip_ms"], d["untrimmed_ms"], d["dense_ms"] = timed((skip, untrim, dense))
+        d = {"max_rel_diff_untrimmed": close(got_untrim(), want()), "max_rel_diff_untrimmed_materialised": close(got_mat(), want()),
+             "max_rel_diff_dense": close(got_dense(), want())}
+        d["skip_ms"], d["untrimmed_ms"], d["untrimmed_materialised_ms"], d["dense_ms"] = timed((skip, untrim, mat, dense))
         d["gain_of_trimming"] = d["untrimmed_ms"] / d["skip_ms"]
         d["gain_over_dense"] = d["dense_ms"] / d["skip_ms"]
         return d
 
+    sp, pp = (s, s), (p, p)
+
     # ConvV2 | plain convolution = the dense form: the padded input, padding 0
     Xp = F.pad(B.X, (0, 0, p, p, p, p)).contiguous()
     Y2 = torch.empty_like(B.Y)
+    Y1 = torch.empty_like(B.Y)
     plain = lambda: cks.cks_conv2d_fwd(Xp, B.W, Y2, s, 0)
-    out["conv2d_fwd"] = row(B.fwd, plain, plain, lambda: Y2, lambda: Y2, lambda: B.Y)
+    out["conv2d_fwd"] = row(B.fwd, lambda: cks.cks_conv2d_fwd_untrimmed_hw(B.X, B.W, Y1, sp, pp), plain, plain,
+                            lambda: Y1, lambda: Y2, lambda: Y2, lambda: B.Y)
     # KS-deconv-V2 | KS-deconv (Algorithm 2) | zero-inserted gradient on a zero canvas, rotated filter, unit stride
-    dX1 = torch.empty_like(B.dX)
+    dX1, dX0 = torch.empty_like(B.dX), torch.empty_like(B.dX)
     alg2 = untrimmed.prepare_deconv2d(cks, B.dY, B.W, dX1, s, p)
     Z = torch.zeros((L.N, L.IH + L.FH - 1, L.IW + L.FW - 1, L.OC), device=B.X.device)
     o = (L.FH - 1 - p, L.FW - 1 - p)
@@ -404,10 +413,11 @@ def ablation(L, steps, warmup):
     Z[:, ih[mh][:, None], iw[mw][None, :], :] = B.dY[:, mh][:, :, mw]
     Wr = B.W.flip(1, 2).permute(3, 1, 2, 0).contiguous()      # [IC, FH, FW, OC]
     dX2 = torch.empty_like(B.dX)
-    out["deconv2d"] = row(B.deconv, alg2, lambda: cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0), lambda: dX1, lambda: dX2, lambda: B.dX)
+    out["deconv2d"] = row(B.deconv, lambda: cks.cks_deconv2d_untrimmed_hw(B.dY, B.W, dX0, sp, pp), alg2,
+                          lambda: cks.cks_conv2d_fwd(Z, Wr, dX2, 1, 0), lambda: dX0, lambda: dX1, lambda: dX2, lambda: B.dX)
     # Sk-dilated-V2 | Sk-dilated (Algorithm 3) | the dilated gradient as the filter of a unit-stride convolution
     # over the padded input (image axis and channel axis change places: the contraction runs over n)
-    dW1 = torch.empty_like(B.dW)
+    dW1, dW0 = torch.empty_like(B.dW), torch.empty_like(B.dW)
     alg3 = untrimmed.prepare_dilated_conv2d_wgrad(cks, B.X, B.dY, dW1, s, p)
     D = torch.zeros((L.N, hs, ws, L.OC), device=B.X.device)
     D[:, ::s, ::s, :] = B.dY
@@ -415,8 +425,9 @@ def ablation(L, steps, warmup):
     Xq = Xp[:, :need_h, :need_w, :].permute(3, 1, 2, 0).contiguous()   # [IC, rows, cols, N]
     Dq = D.permute(3, 1, 2, 0).contiguous()                            # [OC, hs, ws, N]
     dWq = torch.empty((L.IC, L.FH, L.FW, L.OC), device=B.X.device)
-    out["dilated_conv2d_wgrad"] = row(B.wgrad, alg3, lambda: cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0),
-                                      lambda: dW1, lambda: dWq.permute(3, 1, 2, 0), lambda: B.dW)
+    out["dilated_conv2d_wgrad"] = row(B.wgrad, lambda: cks.cks_dilated_conv2d_wgrad_untrimmed_hw(B.X, B.dY, dW0, sp, pp, B.ws_wgrad), alg3,
+                                      lambda: cks.cks_conv2d_fwd(Xq, Dq, dWq, 1, 0),
+                                      lambda: dW0, lambda: dW1, lambda: dWq.permute(3, 1, 2, 0), lambda: B.dW)
     return out
 
 

@@ -54,7 +54,8 @@ typedef enum {
     CKS_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than the *_workspace() size */
     CKS_ERR_HIP = -4,         /* a HIP runtime call failed; see cks_last_hip_error() */
     CKS_ERR_UNSUPPORTED = -5, /* valid geometry that this entry point has no kernel for
-                                 (cks_conv2d_fwd_transposed; unknown op of cks_plan_hw) */
+                                 (cks_conv2d_fwd_transposed, the *_untrimmed entry points;
+                                 unknown op of cks_plan_hw) */
     CKS_ERR_SCRATCH = -6      /* cks_dilated_conv2d_wgrad_noalloc_hw: the call needs more than
                                  CKS_STATIC_SCRATCH_BYTES of scratch memory */
 } cks_status;
@@ -240,6 +241,35 @@ int cks_dilated_conv2d_wgrad_partials_hw(const float *X, const float *dY, float 
  * for e < elems (= OC*FH*FW*C), segments >= 1. */
 int cks_reduce_partials(const float *part, float *dW, int64_t elems, int segments, void *stream);
 
+/* ---- the operators with filter trimming switched off (for the ablation) ----
+ *
+ * Sections IV.A-IV.C introduce each operator first without trimming -- the plain
+ * convolution, KS-deconv (Algorithm 2: kernel split only) and Sk-dilated
+ * (Algorithm 3: leaping access only) -- and then its V2 with the filter / range
+ * trimmed (Algorithms 1, 2B, 3B).  These entry points run the former through the
+ * same kernels, work lists and segment counts as the library's operators: every
+ * position (every tap) contracts its whole window, and the cells of the window
+ * that lie outside the data are fetched as zeros and multiplied.  Results equal
+ * those of the trimmed operators up to the order of the fp32 sums (exactly, on
+ * integer-valued inputs).  They exist for the kernels that load their operands
+ * straight into LDS only.  Forward and input gradient: C and OC multiples of 32,
+ * a tile 64 columns wide (OC >= 48 forward, C >= 48 input gradient), 16-byte
+ * aligned tensors.  Filter gradient: N a multiple of 32, C and OC multiples of 4,
+ * 16-byte aligned tensors, and a geometry for which the library's own filter
+ * gradient takes its general kernel (not the one for small images).  Any other
+ * call returns CKS_ERR_UNSUPPORTED with nothing enqueued.  Tensors, H/W convention, stream and
+ * (filter gradient) workspace as for cks_conv2d_fwd_hw, cks_deconv2d_hw (no
+ * workspace: the filter is read in place) and cks_dilated_conv2d_wgrad_hw. */
+int cks_conv2d_fwd_untrimmed_hw(const float *X, const float *Wt, float *Y,
+                                int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                void *stream);
+int cks_deconv2d_untrimmed_hw(const float *dY, const float *Wt, float *dX,
+                              int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                              void *stream);
+int cks_dilated_conv2d_wgrad_untrimmed_hw(const float *X, const float *dY, float *dW,
+                                          int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                          void *ws, size_t ws_bytes, void *stream);
+
 /* ---- which kernels a call would enqueue (host only, no device is touched) ----
  *
  * Which kernel variant serves a call is a function of the geometry and of the
@@ -264,7 +294,10 @@ typedef enum {
     CKS_OP_FILTER_TRANSPOSE = 5,
     CKS_OP_WGRAD_PARTIALS = 6,
     CKS_OP_REDUCE_PARTIALS = 7,
-    CKS_OP_CONV2D_FWD_TRANSPOSED = 8
+    CKS_OP_CONV2D_FWD_TRANSPOSED = 8,
+    CKS_OP_CONV2D_FWD_UNTRIMMED = 9,
+    CKS_OP_DECONV2D_UNTRIMMED = 10,
+    CKS_OP_WGRAD_UNTRIMMED = 11
 } cks_op;
 int cks_plan_hw(int op, int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                 unsigned only_4byte_aligned, char *text, size_t text_bytes);

@@ -17,7 +17,8 @@ _lib = None
 CKS_OK, CKS_ERR_NULL, CKS_ERR_SHAPE, CKS_ERR_WORKSPACE, CKS_ERR_HIP, CKS_ERR_UNSUPPORTED, CKS_ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6
 CKS_STATIC_SCRATCH_BYTES = 32 << 20
 (CKS_OP_CONV2D_FWD, CKS_OP_DECONV2D, CKS_OP_DILATED_CONV2D_WGRAD, CKS_OP_KERNEL_SPLIT, CKS_OP_DECONV2D_PRESPLIT,
- CKS_OP_FILTER_TRANSPOSE, CKS_OP_WGRAD_PARTIALS, CKS_OP_REDUCE_PARTIALS, CKS_OP_CONV2D_FWD_TRANSPOSED) = range(9)
+ CKS_OP_FILTER_TRANSPOSE, CKS_OP_WGRAD_PARTIALS, CKS_OP_REDUCE_PARTIALS, CKS_OP_CONV2D_FWD_TRANSPOSED,
+ CKS_OP_CONV2D_FWD_UNTRIMMED, CKS_OP_DECONV2D_UNTRIMMED, CKS_OP_WGRAD_UNTRIMMED) = range(12)
 
 _GEO = [ctypes.c_int] * 9
 _GEO_HW = [ctypes.c_int] * 11   # N, C, H, W, OC, FH, FW, sh, sw, ph, pw
@@ -54,6 +55,9 @@ _PROTOTYPES = {
     "cks_dilated_conv2d_wgrad_noalloc_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
     "cks_conv2d_fwd_transposed": ([ctypes.c_void_p] * 3 + _GEO + [ctypes.c_void_p], ctypes.c_int),
     "cks_conv2d_fwd_transposed_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_conv2d_fwd_untrimmed_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_deconv2d_untrimmed_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + [ctypes.c_void_p], ctypes.c_int),
+    "cks_dilated_conv2d_wgrad_untrimmed_hw": ([ctypes.c_void_p] * 3 + _GEO_HW + _OP_TAIL, ctypes.c_int),
     "cks_plan_hw": ([ctypes.c_int] + _GEO_HW + [ctypes.c_uint, ctypes.c_char_p, ctypes.c_size_t], ctypes.c_int),
     "cks_strerror": ([ctypes.c_int], ctypes.c_char_p),
     "cks_last_hip_error": ([], ctypes.c_int),
@@ -365,3 +369,34 @@ def cks_conv2d_fwd_transposed_hw(X, Wtt, Y, stride, padding):
     _check(lib().cks_conv2d_fwd_transposed_hw(_ptr(X, "X"), _ptr(Wtt, "Wtt", (FH, FW, C, OC)), _ptr(Y, "Y", (N, OH, OW, OC)),
                                               N, C, H, W, OC, FH, FW, *stride, *padding, _stream()), "cks_conv2d_fwd_transposed_hw")
     return Y
+
+
+# ---- trimming switched off (ablation): stride = (sh, sw), padding = (ph, pw)
+
+def cks_conv2d_fwd_untrimmed_hw(X, Wt, Y, stride, padding):
+    N, H, W, C = X.shape
+    OC, FH, FW, _ = Wt.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    _check(lib().cks_conv2d_fwd_untrimmed_hw(_ptr(X, "X"), _ptr(Wt, "Wt", (OC, FH, FW, C)), _ptr(Y, "Y", (N, OH, OW, OC)),
+                                             N, C, H, W, OC, FH, FW, *stride, *padding, _stream()), "cks_conv2d_fwd_untrimmed_hw")
+    return Y
+
+
+def cks_deconv2d_untrimmed_hw(dY, Wt, dX, stride, padding):
+    N, H, W, C = dX.shape
+    OC, FH, FW, _ = Wt.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    _check(lib().cks_deconv2d_untrimmed_hw(_ptr(dY, "dY", (N, OH, OW, OC)), _ptr(Wt, "Wt", (OC, FH, FW, C)), _ptr(dX, "dX"),
+                                           N, C, H, W, OC, FH, FW, *stride, *padding, _stream()), "cks_deconv2d_untrimmed_hw")
+    return dX
+
+
+def cks_dilated_conv2d_wgrad_untrimmed_hw(X, dY, dW, stride, padding, ws):
+    N, H, W, C = X.shape
+    OC, FH, FW, _ = dW.shape
+    OH, OW = cks_out_dims_hw(H, W, FH, FW, stride, padding)
+    wp, wb = _ws(ws)
+    _check(lib().cks_dilated_conv2d_wgrad_untrimmed_hw(_ptr(X, "X"), _ptr(dY, "dY", (N, OH, OW, OC)), _ptr(dW, "dW", (OC, FH, FW, C)),
+                                                       N, C, H, W, OC, FH, FW, *stride, *padding, wp, wb, _stream()),
+           "cks_dilated_conv2d_wgrad_untrimmed_hw")
+    return dW

@@ -201,8 +201,10 @@ int launch(const KName &name, K kernel, const P &params, int blocks, size_t lds,
 
 // ---------------------------------------------------------------- ConvV2 / KS-deconv Stage 2&3
 
+// untrimmed: the ablation's operators without filter trimming (plain convolution, KS-deconv of Algorithm 2); they
+// exist for the 64x64 tile loaded straight into LDS only.
 template <int OP, int BM, int BN, int WM, int WN>
-int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
+int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st, bool untrimmed = false)
 {
     P.mTiles = (rows + BM - 1) / BM;
     P.nTiles = (cols + BN - 1) / BN;
@@ -259,17 +261,26 @@ int launch_rowrun(RowRunParams P, int rows, int cols, bool vec, hipStream_t st)
     // (kernels that only a tuning build can select are not instantiated otherwise)
     const bool dma = kHasDma && !tune("CKS_TUNE_NO_LDS_DIRECT");
     constexpr bool kAlwaysDma = kHasDma && !kTuning;
+    if (untrimmed) {
+        if constexpr ((OP == OP_FWD || OP == OP_DECONV_W) && BM == 64 && BN == 64) {
+            const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (OP == OP_DECONV_W || (rowB * BN + rowB) * 4 < (1LL << 31));
+            if (fast)
+                return launch(with_bools(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), false), rowrun_gemm_dma<OP, BM, BN, WM, WN, false>, P,
+                              (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
+        }
+        return CKS_ERR_UNSUPPORTED;
+    }
     if constexpr (op_b_k_major(OP)) {
         // the caller has checked deconv_in_place_ok / fwd_transposed_ok: only the fast-load variants exist
         if constexpr (kHasDma)
-            if (dma) return launch(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
+            if (dma) return launch(with_bools(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), true), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
         if constexpr (!kAlwaysDma)
             return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_FAST), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
     } else {
         const bool fast = vec && kch % 32 == 0 && (rowA * BM + rowA) * 4 < (1LL << 31) && (rowB * BN + rowB) * 4 < (1LL << 31) &&
                           !tune("CKS_TUNE_NO_FAST_LOADS");
         if constexpr (kHasDma)
-            if (fast && dma) return launch(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
+            if (fast && dma) return launch(with_bools(kname("rowrun_gemm_dma", OP, BM, BN, WM, WN), true), rowrun_gemm_dma<OP, BM, BN, WM, WN>, P, (int)blocks, rowrun_dma_lds_bytes<BM, BN>(), st);
         if constexpr (!kAlwaysDma)
             if (fast) return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_FAST), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_FAST>, P, (int)blocks, lds, st);
         if (vec) return launch(kname("rowrun_gemm", OP, BM, BN, WM, WN, LOAD_VEC), rowrun_gemm<OP, BM, BN, WM, WN, LOAD_VEC>, P, (int)blocks, lds, st);
@@ -289,7 +300,7 @@ bool deconv_in_place_ok(const Geo &g, const float *dY, const float *Wt)
 }
 
 template <int OP>
-int dispatch_rowrun(const RowRunParams &P, int rows, int cols, bool vec, hipStream_t st)
+int dispatch_rowrun(const RowRunParams &P, int rows, int cols, bool vec, hipStream_t st, bool untrimmed = false)
 {
     const long long positions = (long long)P.itemsH * P.itemsW;
     // rows = batch, cols = output channels of this operator.  Measured on all
@@ -306,8 +317,8 @@ int dispatch_rowrun(const RowRunParams &P, int rows, int cols, bool vec, hipStre
     if (bm == 128 && bn == 64) return launch_rowrun<OP, 128, 64, 2, 2>(P, rows, cols, vec, st);
     if (bm == 64 && bn == 128) return launch_rowrun<OP, 64, 128, 2, 2>(P, rows, cols, vec, st);
 #endif
-    if (bm == 64 && bn == 64) return launch_rowrun<OP, 64, 64, 2, 2>(P, rows, cols, vec, st);
-    return launch_rowrun<OP, 128, 32, 4, 1>(P, rows, cols, vec, st);
+    if (bm == 64 && bn == 64) return launch_rowrun<OP, 64, 64, 2, 2>(P, rows, cols, vec, st, untrimmed);
+    return launch_rowrun<OP, 128, 32, 4, 1>(P, rows, cols, vec, st, untrimmed);
 }
 
 template <int OP>
@@ -524,7 +535,7 @@ WgradPlan plan_wgrad(const Geo &g)
 }
 
 template <int BM, int BN, int KC, int WM, int WN, int WK>
-int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
+int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st, bool untrimmed = false)
 {
     const size_t lds = pixel_lds_bytes<BM, BN, KC>();
     const int blocks = P.perXcd * kXcds;
@@ -547,9 +558,11 @@ int launch_pixel(PixelGemmParams P, bool veca, bool vecb, hipStream_t st)
         // the default tile also exists with its chunks (32 images) loaded straight into LDS
         if (fast && P.N % kPixelDmaKC == 0 && !tune("CKS_TUNE_NO_LDS_DIRECT")) {
             P.dNC = make_fastdiv(P.N / kPixelDmaKC);
-            return launch(kname("pixel_gemm_dma"), pixel_gemm_dma, P, blocks, pixel_dma_lds_bytes(), st);
+            if (untrimmed) return launch(with_bools(kname("pixel_gemm_dma"), false), pixel_gemm_dma<false>, P, blocks, pixel_dma_lds_bytes(), st);
+            return launch(with_bools(kname("pixel_gemm_dma"), true), pixel_gemm_dma<true>, P, blocks, pixel_dma_lds_bytes(), st);
         }
     }
+    if (untrimmed) return CKS_ERR_UNSUPPORTED;   // Algorithm 3 exists for the tile loaded straight into LDS only
     if (fast) return launch(kname("pixel_gemm_fast", BM, BN, KC, WM, WN, WK), pixel_gemm_fast<BM, BN, KC, WM, WN, WK>, P, blocks, lds, st);
     if (veca && vecb) return launch(with_bools(kname("pixel_gemm", BM, BN, KC, WM, WN, WK), true, true), pixel_gemm<BM, BN, KC, WM, WN, WK, true, true>, P, blocks, lds, st);
     if (veca) return launch(with_bools(kname("pixel_gemm", BM, BN, KC, WM, WN, WK), true, false), pixel_gemm<BM, BN, KC, WM, WN, WK, true, false>, P, blocks, lds, st);
@@ -722,6 +735,23 @@ int conv_fwd_transposed(const Geo &g, const float *X, const float *Wtt, float *Y
     return dispatch_rowrun<OP_FWD_T>(rowrun_params<OP_FWD_T>(g, X, Wtt, Y), g.N, g.OC, true, st);
 }
 
+// The operators with filter trimming switched off (Section IV: the plain convolution that ConvV2 improves on, and
+// KS-deconv as Algorithm 2 states it before the V2 of Algorithm 2B), for the ablation.  Same kernels, same work
+// lists; every position contracts its whole window and the cells outside the data are read as zeros.
+int conv_fwd_untrimmed(const Geo &g, const float *X, const float *Wt, float *Y, hipStream_t st)
+{
+    if (!X || !Wt || !Y) return CKS_ERR_NULL;
+    if (g.OC < 48 || g.C % 4 != 0 || !aligned16(X) || !aligned16(Wt)) return CKS_ERR_UNSUPPORTED;
+    return dispatch_rowrun<OP_FWD>(rowrun_params<OP_FWD>(g, X, Wt, Y), g.N, g.OC, true, st, true);
+}
+
+int deconv_untrimmed(const Geo &g, const float *dY, const float *Wt, float *dX, hipStream_t st)
+{
+    if (!dY || !Wt || !dX) return CKS_ERR_NULL;
+    if (g.C < 48 || !deconv_in_place_ok(g, dY, Wt)) return CKS_ERR_UNSUPPORTED;
+    return dispatch_rowrun<OP_DECONV_W>(rowrun_params<OP_DECONV_W>(g, dY, Wt, dX), g.N, g.C, true, st, true);
+}
+
 int kernel_split(const float *Wt, float *Cs, int C, int OC, int FH, int FW, int sh, int sw, hipStream_t st)
 {
     if (C <= 0 || OC <= 0 || FH <= 0 || FW <= 0 || sh < 1 || sw < 1 || sh > (1 << 20) || sw > (1 << 20)) return CKS_ERR_SHAPE;
@@ -788,11 +818,12 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
     return deconv_presplit(g, dY, (const float *)ws, dX, st);
 }
 
-int wgrad_partials(const Geo &g, const float *X, const float *dY, float *part, hipStream_t st)
+int wgrad_partials(const Geo &g, const float *X, const float *dY, float *part, hipStream_t st, bool untrimmed = false)
 {
     if (!X || !dY || !part) return CKS_ERR_NULL;
     const int N = g.N, C = g.C, H = g.H, W = g.W, OC = g.OC, FH = g.FH, FW = g.FW;
     const WgradPlan w = plan_wgrad(g);
+    if (untrimmed && (w.patch || w.variant != 4)) return CKS_ERR_UNSUPPORTED;
     const bool veca = (OC % 4 == 0) && aligned16(dY);
     const bool vecb = (C % 4 == 0) && aligned16(X);
     if (w.patch == 4) {
@@ -837,21 +868,21 @@ int wgrad_partials(const Geo &g, const float *X, const float *dY, float *part, h
         case 3: return launch_pixel<64, 64, 32, 1, 1, 4>(P, veca, vecb, st);
         case 6: return launch_pixel<64, 128, 16, 2, 2, 1>(P, veca, vecb, st);
 #endif
-        case 4: return launch_pixel<64, 64, 16, 2, 2, 1>(P, veca, vecb, st);
+        case 4: return launch_pixel<64, 64, 16, 2, 2, 1>(P, veca, vecb, st, untrimmed);
         case 5: return launch_pixel<128, 64, 16, 2, 2, 1>(P, veca, vecb, st);
         default: return CKS_ERR_UNSUPPORTED;
     }
 }
 
-int wgrad(const Geo &g, const float *X, const float *dY, float *dW, void *ws, size_t ws_bytes, void *stream)
+int wgrad(const Geo &g, const float *X, const float *dY, float *dW, void *ws, size_t ws_bytes, void *stream, bool untrimmed = false)
 {
     if (!X || !dY || !dW) return CKS_ERR_NULL;
     const int GZ = plan_wgrad(g).GZ;
     const long slice = (long)g.OC * g.FH * g.FW * g.C;
     if (GZ == 1)  // one segment: its "partial" result is the result
-        return wgrad_partials(g, X, dY, dW, (hipStream_t)stream);
+        return wgrad_partials(g, X, dY, dW, (hipStream_t)stream, untrimmed);
     if (!ws || ws_bytes < sizeof(float) * (size_t)GZ * slice) return CKS_ERR_WORKSPACE;
-    int rc = wgrad_partials(g, X, dY, (float *)ws, (hipStream_t)stream);
+    int rc = wgrad_partials(g, X, dY, (float *)ws, (hipStream_t)stream, untrimmed);
     if (rc != CKS_OK) return rc;
     return cks_reduce_partials((const float *)ws, dW, slice, GZ, stream);
 }
@@ -1045,6 +1076,36 @@ int cks_conv2d_fwd_transposed(const float *X, const float *Wtt, float *Y,
     return cks_conv2d_fwd_transposed_hw(X, Wtt, Y, N, C, H, W, OC, FH, FW, stride, stride, padding, padding, stream);
 }
 
+int cks_conv2d_fwd_untrimmed_hw(const float *X, const float *Wt, float *Y,
+                                int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return conv_fwd_untrimmed(g, X, Wt, Y, (hipStream_t)stream);
+}
+
+int cks_deconv2d_untrimmed_hw(const float *dY, const float *Wt, float *dX,
+                              int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                              void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return deconv_untrimmed(g, dY, Wt, dX, (hipStream_t)stream);
+}
+
+int cks_dilated_conv2d_wgrad_untrimmed_hw(const float *X, const float *dY, float *dW,
+                                          int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
+                                          void *ws, size_t ws_bytes, void *stream)
+{
+    Geo g;
+    int rc = check_geo(g, N, C, H, W, OC, FH, FW, sh, sw, ph, pw);
+    if (rc != CKS_OK) return rc;
+    return wgrad(g, X, dY, dW, ws, ws_bytes, stream, true);
+}
+
 int cks_deconv2d_presplit_hw(const float *dY, const float *Cs, float *dX,
                              int N, int C, int H, int W, int OC, int FH, int FW, int sh, int sw, int ph, int pw,
                              void *stream)
@@ -1133,6 +1194,9 @@ int cks_plan_hw(int op, int N, int C, int H, int W, int OC, int FH, int FW, int 
         case CKS_OP_WGRAD_PARTIALS: rc = wgrad_partials(g, a, b, c, nullptr); break;
         case CKS_OP_REDUCE_PARTIALS: rc = cks_reduce_partials(a, b, (int64_t)OC * FH * FW * C, plan_wgrad(g).GZ, nullptr); break;
         case CKS_OP_CONV2D_FWD_TRANSPOSED: rc = conv_fwd_transposed(g, a, b, c, nullptr); break;
+        case CKS_OP_CONV2D_FWD_UNTRIMMED: rc = conv_fwd_untrimmed(g, a, b, c, nullptr); break;
+        case CKS_OP_DECONV2D_UNTRIMMED: rc = deconv_untrimmed(g, a, b, c, nullptr); break;
+        case CKS_OP_WGRAD_UNTRIMMED: rc = wgrad(g, a, b, c, ws, wgrad_workspace(g), nullptr, true); break;
         default: rc = CKS_ERR_UNSUPPORTED; break;
     }
     g_plan = nullptr;

@@ -62,6 +62,9 @@ __device__ __forceinline__ void pixel_dma_pairs(unsigned a_addr, unsigned b_addr
 }
 
 // 64 x 64 tile, 2 x 2 waves of one 32x32 block each, P.dNC = N / 32.
+// TRIM = false: Sk-dilated before its V2 (Algorithm 3), for the ablation -- every tap visits all (oh,ow), and a
+// chunk whose leaped-to X pixel lies outside the input is fetched through a descriptor of zero length, i.e. as zeros.
+template <bool TRIM = true>
 __global__ void __launch_bounds__(kThreads) pixel_gemm_dma(const PixelGemmParams P)
 {
     constexpr int BM = 64, BN = 64, KC = kPixelDmaKC;
@@ -82,8 +85,8 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_dma(const PixelGemmParams
     const int ih_s = fh - P.ph, iw_s = fw - P.pw;
     const int shiftK = P.FH + P.FW;
     auto cdiv_s = [&](int a, const FastDiv &d) { return fdiv(a + shiftK * d.d + d.d - 1, d) - shiftK; };
-    const int oh_s = max(cdiv_s(-ih_s, P.dSh), 0), oh_e = min(P.OH, cdiv_s(P.IH - ih_s, P.dSh));
-    const int ow_s = max(cdiv_s(-iw_s, P.dSw), 0), ow_e = min(P.OW, cdiv_s(P.IW - iw_s, P.dSw));
+    const int oh_s = TRIM ? max(cdiv_s(-ih_s, P.dSh), 0) : 0, oh_e = TRIM ? min(P.OH, cdiv_s(P.IH - ih_s, P.dSh)) : P.OH;
+    const int ow_s = TRIM ? max(cdiv_s(-iw_s, P.dSw), 0) : 0, ow_e = TRIM ? min(P.OW, cdiv_s(P.IW - iw_s, P.dSw)) : P.OW;
     const int nOH = max(oh_e - oh_s, 0), nOW = max(ow_e - ow_s, 0);
     const int NC = P.dNC.d;                        // chunks per (oh,ow): N / 32
     const int Ct = nOH * nOW * NC;                 // chunks of this tap
@@ -121,10 +124,13 @@ __global__ void __launch_bounds__(kThreads) pixel_gemm_dma(const PixelGemmParams
         const int oh = oh_s + pa_, ow = ow_s + pb_, n1 = nch * KC;
         const int sa = (((n1 * P.OH + oh) * P.OW + ow) * P.OC) * 4;
         const int sb = (((n1 * P.IH + oh * P.sh + ih_s) * P.IW + ow * P.sw + iw_s) * P.IC) * 4;
+        // untrimmed: a pixel outside the input is read through a descriptor of length 0 (wave-uniform: one scalar select)
+        const bool inside = TRIM || ((unsigned)(oh * P.sh + ih_s) < (unsigned)P.IH && (unsigned)(ow * P.sw + iw_s) < (unsigned)P.IW);
+        const __amdgpu_buffer_rsrc_t rsBc = TRIM ? rsB : __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.X), 0, __builtin_amdgcn_readfirstlane(inside ? -1 : 0), 0x00020000);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             load16_to_lds(rsA, As + buf * KC * BM + (2 * wave + q) * 256, va[q], sa);
-            load16_to_lds(rsB, Bs + buf * KC * BN + (2 * wave + q) * 256, vb[q], sb);
+            load16_to_lds(rsBc, Bs + buf * KC * BN + (2 * wave + q) * 256, vb[q], sb);
         }
         if (++nch == NC) { nch = 0; if (++pb_ == nOW) { pb_ = 0; ++pa_; } }
     };

@@ -35,7 +35,10 @@ namespace cks {
 template <int BM, int BN>
 constexpr size_t rowrun_dma_lds_bytes() { return (size_t)2 * (BM + BN) * 32 * sizeof(float); }
 
-template <int OP, int BM, int BN, int WAVES_M, int WAVES_N>
+// TRIM = false: the ablation's untrimmed operators (plain convolution; KS-deconv of Algorithm 2) -- every
+// position contracts its whole window, and a chunk whose A pixel lies outside the data is fetched through a
+// descriptor of zero length, i.e. as zeros, which the matrix cores then multiply like any other operand.
+template <int OP, int BM, int BN, int WAVES_M, int WAVES_N, bool TRIM = true>
 __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P)
 {
     constexpr int KC = 32;
@@ -68,7 +71,7 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int frow = lane & 31, h = lane >> 5;
 
-    const RunSet R = decode_position<OP>(P, ph, pw);
+    const RunSet R = decode_position<OP, TRIM>(P, ph, pw);
     const int cpr = R.L / KC;             // chunks per run (the host launches this kernel only if L % 32 == 0)
     const int T = R.nruns * cpr;
 
@@ -107,25 +110,28 @@ __global__ void __launch_bounds__(kThreads) rowrun_gemm_dma(const RowRunParams P
             vb[q] = (unsigned)(((long)(c - min(n0, R.NC - 1)) * R.strideB + piece * 4) * 4);
         }
     }
-    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(P.A + (long)min(m0, P.N - 1) * R.strideA + R.a0), 0, -1, 0x00020000);
+    float *const baseA = const_cast<float *>(P.A + (long)min(m0, P.N - 1) * R.strideA + R.a0);
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(baseA, 0, -1, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsB =
         BK ? __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + n0), 0, (int)(((long)P.OC * P.FH * P.FW * P.IC - n0) * 4), 0x00020000)
            : __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.B + (long)min(n0, R.NC - 1) * R.strideB + R.b0), 0, -1, 0x00020000);
-    const int ocChunks = (op_is_fwd(OP) ? P.IC : P.OC) / KC;   // BK: chunks per tap of a run (the contracted channels)
+    const int ocChunks = (op_is_fwd(OP) ? P.IC : P.OC) / KC;   // chunks per tap of a run (the contracted channels)
 
-    int run = 0, ck = 0, cwi = 0, occ = 0;   // chunk being loaded (BK: output channels 32*occ.. of sub-kernel column cw_s + cwi)
+    int run = 0, ck = 0, cwi = 0, occ = 0;   // chunk being loaded: contracted channels 32*occ.. of the run's tap number cwi
     auto next_chunk = [&]() {
-        if (BK && ++occ == ocChunks) { occ = 0; ++cwi; }
+        if ((BK || !TRIM) && ++occ == ocChunks) { occ = 0; ++cwi; }
         if (++ck == cpr) { ck = 0; ++run; cwi = 0; occ = 0; }
     };
     auto gload = [&](int buf) {   // buf is a literal at every call
         const int sa = (int)((run * R.aRun + ck * KC) * 4);
+        // untrimmed: a chunk outside the data is read through a descriptor of length 0 (wave-uniform: one scalar select)
+        const bool inside = TRIM || ((unsigned)(R.h0 + run) < (unsigned)R.hLim && (unsigned)(R.w0 + cwi) < (unsigned)R.wLim);
+        const __amdgpu_buffer_rsrc_t rsAc = TRIM ? rsA : __builtin_amdgcn_make_buffer_rsrc(baseA, 0, __builtin_amdgcn_readfirstlane(inside ? -1 : 0), 0x00020000);
         const int sb = BK ? (int)((R.b0 + run * R.bRun + cwi * R.bCw + (long)occ * KC * R.strideB) * 4)
                           : (int)((run * R.bRun + ck * KC) * 4);
 #pragma unroll
         for (int q = 0; q < IA; ++q)
-            load16_to_lds(rsA, As + buf * BM * KC + (IA * wave + q) * 256, va[q], sa);
+            load16_to_lds(rsAc, As + buf * BM * KC + (IA * wave + q) * 256, va[q], sa);
 #pragma unroll
         for (int q = 0; q < IB; ++q)
             load16_to_lds(rsB, Bs + buf * BN * KC + (IB * wave + q) * 256, vb[q], sb);

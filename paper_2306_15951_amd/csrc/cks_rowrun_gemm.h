@@ -67,6 +67,9 @@ struct RunSet {
     long bCw;                 // OP_DECONV_W: float distance between consecutive cw (negative: the rotation)
     long strideA, strideB, strideO;
     int nruns, L, NC;         // runs, floats per run, number of output channels
+    // untrimmed variant only: run r, tap column c of the window is A pixel (h0 + r, w0 + c), which exists if
+    // it lies inside hLim x wLim (Algorithm 2 / the plain convolution read zeros elsewhere)
+    int h0, w0, hLim, wLim;
 };
 
 // The a-th index of [0, I) when indices are listed class by class, class
@@ -100,7 +103,9 @@ __device__ inline int class_major_index(int a, int I, const FastDiv &dS, int pmo
 
 // Trim and addressing of one output position: (oh,ow) of Y for ConvV2, (ih,iw)
 // of dX for KS-deconv.
-template <int OP>
+// TRIM = false: the whole window is contracted, as in the plain convolution and in KS-deconv before its V2
+// (Algorithm 2); the caller supplies zeros for the window's cells outside the data.
+template <int OP, bool TRIM = true>
 __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
 {
     RunSet R;
@@ -111,6 +116,8 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         int ih_s = oh * P.sh - P.ph, iw_s = ow * P.sw - P.pw;
         int fh_s = max(-ih_s, 0), fh_e = min(P.IH - ih_s, P.FH);
         int fw_s = max(-iw_s, 0), fw_e = min(P.IW - iw_s, P.FW);
+        if (!TRIM) { fh_s = 0; fh_e = P.FH; fw_s = 0; fw_e = P.FW; }
+        R.h0 = ih_s; R.w0 = iw_s; R.hLim = P.IH; R.wLim = P.IW;
         R.nruns = max(fh_e - fh_s, 0);
         R.L = max(fw_e - fw_s, 0) * P.IC;
         R.a0 = ((long)(ih_s + fh_s) * P.IW + (iw_s + fw_s)) * P.IC;
@@ -142,6 +149,8 @@ __device__ inline RunSet decode_position(const RowRunParams &P, int ph, int pw)
         int oh_s = qh - (CH - 1), ow_s = qw - (CW - 1);
         int ch_s = max(-oh_s, 0), ch_e = min(P.OH - oh_s, CH);
         int cw_s = max(-ow_s, 0), cw_e = min(P.OW - ow_s, CW);
+        if (!TRIM) { ch_s = 0; ch_e = CH; cw_s = 0; cw_e = CW; }
+        R.h0 = oh_s; R.w0 = ow_s; R.hLim = P.OH; R.wLim = P.OW;
         R.nruns = max(ch_e - ch_s, 0);
         R.L = max(cw_e - cw_s, 0) * P.OC;
         R.a0 = ((long)(oh_s + ch_s) * P.OW + (ow_s + cw_s)) * P.OC;

@@ -26,12 +26,12 @@ int main()
                 for (int ph = 0; ph <= 7; ph += (ph < 3 ? 1 : 4))
                     for (int pw = ph; pw <= ph + 2; pw += 2) {
                         const bool valid = s[2] + 2 * ph >= s[5] && s[3] + 2 * pw >= s[6];
-                        for (int op = 0; op <= 8; ++op)
+                        for (int op = 0; op <= CKS_OP_WGRAD_UNTRIMMED; ++op)
                             for (unsigned mask = 0; mask < 16; mask += 5) {
                                 const int rc = cks_plan_hw(op, s[0], s[1], s[2], s[3], s[4], s[5], s[6], sh, sw, ph, pw, mask, text, sizeof text);
                                 // the forward pass on the transposed filter exists for whole 32-channel chunks, aligned pointers and
                                 // tile rows within 2 GiB only: on a valid geometry it may also answer that it has no kernel
-                                if (valid && op == CKS_OP_CONV2D_FWD_TRANSPOSED && rc == CKS_ERR_UNSUPPORTED) { ++plans; continue; }
+                                if (valid && op >= CKS_OP_CONV2D_FWD_TRANSPOSED && rc == CKS_ERR_UNSUPPORTED) { ++plans; continue; }
                                 if (valid ? (rc != CKS_OK || !strchr(text, '[')) : rc != CKS_ERR_SHAPE) {
                                     printf("op %d shape %d,%d,%d,%d,%d,%d,%d s %d,%d p %d,%d mask %u: status %d\n", op, s[0], s[1], s[2], s[3],
                                            s[4], s[5], s[6], sh, sw, ph, pw, mask, rc);

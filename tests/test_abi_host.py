@@ -168,4 +168,4 @@ def test_forward_on_the_transposed_filter_refuses_on_the_host(cks):
     assert L.cks_conv2d_fwd_transposed(None, fake, fake, 4, 32, 6, 6, 8, 3, 3, 1, 1, None) == cks.CKS_ERR_NULL
     assert L.cks_conv2d_fwd_transposed_hw(fake, fake, fake, 4, 32, 6, 6, 8, 3, 3, 0, 1, 1, 1, None) == cks.CKS_ERR_SHAPE
     names = [k for k, _ in cks.cks_plan_hw(cks.CKS_OP_CONV2D_FWD_TRANSPOSED, 128, 64, 32, 32, 64, 3, 3, (1, 1), (1, 1))]
-    assert names == ["rowrun_gemm_dma<3, 64, 64, 2, 2>"]
+    assert names == ["rowrun_gemm_dma<3, 64, 64, 2, 2, true>"]

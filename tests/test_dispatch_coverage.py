@@ -66,11 +66,11 @@ def test_plan_of_the_benchmark_layers(cks):
                                               synth.pair(L.stride), synth.pair(L.padding), mask)]
 
     L1, L4b = synth.LAYERS["cfg1"], synth.LAYERS["cfg4b"]
-    assert plan(cks.CKS_OP_CONV2D_FWD, L1) == ["rowrun_gemm_dma<0, 64, 64, 2, 2>"]
-    assert plan(cks.CKS_OP_DECONV2D, L1) == ["rowrun_gemm_dma<2, 64, 64, 2, 2>"]                 # filter read in place: one launch
-    assert plan(cks.CKS_OP_DECONV2D, L1, 2) == ["pack_filter<0>", "rowrun_gemm_dma<1, 64, 64, 2, 2>"]  # Wt off by a float: Stage 1 first
+    assert plan(cks.CKS_OP_CONV2D_FWD, L1) == ["rowrun_gemm_dma<0, 64, 64, 2, 2, true>"]
+    assert plan(cks.CKS_OP_DECONV2D, L1) == ["rowrun_gemm_dma<2, 64, 64, 2, 2, true>"]                 # filter read in place: one launch
+    assert plan(cks.CKS_OP_DECONV2D, L1, 2) == ["pack_filter<0>", "rowrun_gemm_dma<1, 64, 64, 2, 2, true>"]  # Wt off by a float: Stage 1 first
     assert plan(cks.CKS_OP_DECONV2D, L1, 1) == ["pack_filter<0>", "rowrun_gemm<1, 64, 64, 2, 2, 0>"]   # dY off by a float: scalar loads
-    assert plan(cks.CKS_OP_DILATED_CONV2D_WGRAD, L1) == ["pixel_gemm_dma", "reduce_slices<16, 4>"]
+    assert plan(cks.CKS_OP_DILATED_CONV2D_WGRAD, L1) == ["pixel_gemm_dma<true>", "reduce_slices<16, 4>"]
     assert plan(cks.CKS_OP_CONV2D_FWD, L4b) == ["strip_fwd<7, 7, 3, 2>"]
     assert plan(cks.CKS_OP_DECONV2D, L4b) == ["scatter_deconv<10, true>", "add_heads"]
     assert plan(cks.CKS_OP_DILATED_CONV2D_WGRAD, L4b) == ["strip_wgrad<7, 7, 3, 2, true>", "reduce_slices<16, 4>"]

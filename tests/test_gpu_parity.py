@@ -582,6 +582,68 @@ def test_untrimmed_algorithms_through_the_same_kernels(cks, oracle, geo):
         assert_exact(got.cpu().numpy(), w, "%s untrimmed %s" % (L.name, nm))
 
 
+# The same three algorithms as kernel variants with the trimming compiled out (the library's *_untrimmed entry
+# points): whole windows, the cells outside the data fetched as zeros by the loads themselves.  They exist for
+# 32-multiple channel counts only (and, for the filter gradient, a batch that is a multiple of 32).
+TRIM_OFF = [
+    ("trimoff_s1", 64, 64, 7, 6, 64, 3, 3, 1, 1),
+    ("trimoff_s2_4x4", 96, 64, 10, 9, 96, 4, 4, 2, 1),
+    ("trimoff_s3_pad_ragged_batch", 40, 64, 11, 13, 64, 5, 4, 3, 2),
+    ("trimoff_s2_remainder_pad0", 32, 96, 8, 9, 64, 3, 3, 2, 0),
+    ("trimoff_pad_ge_filter", 32, 64, 5, 6, 64, 2, 2, 1, 3),
+    ("trimoff_per_axis_ragged_batch", 70, 64, 9, 12, 128, 3, 5, (2, 1), (1, 2)),
+    ("trimoff_stride_gt_filter", 32, 64, 9, 9, 64, 2, 2, 3, 0),
+]
+
+
+@pytest.mark.parametrize("geo", TRIM_OFF, ids=[g[0] for g in TRIM_OFF])
+def test_kernels_with_trimming_compiled_out(cks, oracle, geo):
+    import torch
+    from paper_2306_15951_amd import synth
+
+    L = synth.Layer(*geo)
+    print("geometry", geo, flush=True)
+    s, p = synth.pair(L.stride), synth.pair(L.padding)
+    for kind in ("int", "normal"):
+        X, W, dY = synth.make_inputs(L, kind, 78)
+        Y, dX, dW = nan_like(dY.shape), nan_like(X.shape), nan_like(W.shape)
+        cks.cks_conv2d_fwd_untrimmed_hw(dev(X), dev(W), Y, s, p)
+        cks.cks_deconv2d_untrimmed_hw(dev(dY), dev(W), dX, s, p)
+        ws = torch.empty(max(cks.cks_dilated_conv2d_wgrad_workspace_hw(L.N, L.IC, L.IH, L.IW, L.OC, L.FH, L.FW, s, p), 4) // 4,
+                         dtype=torch.float32, device="cuda")
+        got = [Y, dX]
+        if L.N % 32 == 0:
+            cks.cks_dilated_conv2d_wgrad_untrimmed_hw(dev(X), dev(dY), dW, s, p, ws)
+            got.append(dW)
+        else:   # no whole 32-image chunks: the variant does not exist, and says so
+            with pytest.raises(cks.CksError) as e:
+                cks.cks_dilated_conv2d_wgrad_untrimmed_hw(dev(X), dev(dY), dW, s, p, ws)
+            assert e.value.status == cks.CKS_ERR_UNSUPPORTED
+        torch.cuda.synchronize()
+        want = oracle_three(oracle, L, X, W, dY)
+        mags = oracle_three(oracle, L, np.abs(X), np.abs(W), np.abs(dY)) if kind == "normal" else want
+        for g, w, m, nm in zip(got, want, mags, ("conv", "KS-deconv", "Sk-dilated")):
+            if kind == "int":
+                assert_exact(g.cpu().numpy(), w, "%s trim-off %s" % (L.name, nm))
+            else:
+                assert_close(g.cpu().numpy(), w, m, "%s trim-off %s" % (L.name, nm))
+
+
+def test_trim_off_variants_say_what_they_cannot_do(cks):
+    import torch
+
+    X = torch.zeros((32, 6, 6, 36), device="cuda")          # 36 channels: no whole 32-channel chunks
+    W = torch.zeros((64, 3, 3, 36), device="cuda")
+    Y = torch.zeros((32, 6, 6, 64), device="cuda")
+    X40, Y40 = torch.zeros((40, 6, 6, 36), device="cuda"), torch.zeros((40, 6, 6, 64), device="cuda")   # 40 images: no whole 32-image chunks
+    for call in (lambda: cks.cks_conv2d_fwd_untrimmed_hw(X, W, Y, (1, 1), (1, 1)),
+                 lambda: cks.cks_deconv2d_untrimmed_hw(Y, W, X, (1, 1), (1, 1)),
+                 lambda: cks.cks_dilated_conv2d_wgrad_untrimmed_hw(X40, Y40, W, (1, 1), (1, 1), torch.zeros(1 << 20, device="cuda"))):
+        with pytest.raises(cks.CksError) as e:
+            call()
+        assert e.value.status == cks.CKS_ERR_UNSUPPORTED
+
+
 GUARD = [
     ("guards", 37, 8, 7, 9, 12, 3, 3, 2, 1),
     ("guards_stem", 5, 3, 23, 26, 64, 7, 7, 2, 3),
@@ -751,7 +813,7 @@ def planned_calls():
     these calls select, and fails if a kernel the library was built with is selected by none of them."""
     from paper_2306_15951_amd import synth
 
-    FWD, DECONV, WGRAD, SPLIT, PRESPLIT_OP, TRANSPOSE, PARTIALS, REDUCE, FWD_T = range(9)
+    FWD, DECONV, WGRAD, SPLIT, PRESPLIT_OP, TRANSPOSE, PARTIALS, REDUCE, FWD_T, FWD_U, DECONV_U, WGRAD_U = range(12)
     calls = []
     three = [tuple(synth.LAYERS["cfg0"])] + MID + RANDOM + ASYM + RANDOM_ASYM + WIDE_TILE
     three += [tuple(synth.LAYERS[n]) for n in FULL] + [("beyond_2GiB", 9, 64, 1024, 1024, 16, 3, 3, 1, 1)]
@@ -768,6 +830,8 @@ def planned_calls():
         calls += [(op, geo, 0) for op in (SPLIT, PRESPLIT_OP)]
     for geo in WGRAD_STAGES:
         calls += [(op, geo, 0) for op in (PARTIALS, REDUCE)]
+    for geo in TRIM_OFF:
+        calls += [(op, geo, 0) for op in ((FWD_U, DECONV_U, WGRAD_U) if geo[1] % 32 == 0 else (FWD_U, DECONV_U))]
     calls.append((WGRAD, tuple(synth.LAYERS["cfg2"]), 0))
     calls.append((DECONV, ("stem_repro", 40, 3, 48, 224, 64, 7, 7, 2, 3), 0))
     return calls
