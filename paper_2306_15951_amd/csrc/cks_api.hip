@@ -20,6 +20,7 @@
 #include "cks_rowrun_dma.h"
 #include "cks_rowrun_gemm.h"
 #include "cks_scatter_deconv.h"
+#include "cks_sweep_deconv.h"
 #include "cks_strip_fwd.h"
 #include "cks_strip_wgrad.h"
 
@@ -670,6 +671,39 @@ ScatterPlan plan_scatter(const Geo &g)
     return S;
 }
 
+// Image-stem KS-deconv on the 4x4x1 matrix instruction (sweep_deconv): the shapes it is built for.
+// 0: none; 1: 7x7 stride 2 padding 3 on the width, 3 input channels, 64 output channels.
+int sweep_geometry(const Geo &g)
+{
+    if (tune("CKS_TUNE_NO_SWEEP")) return 0;
+    if (g.sh != g.sw) return 0;
+    // the two tensors are one raw buffer each, and rows of all windows are counted with 31 bits
+    if ((long long)g.N * g.OH * g.OW * g.OC * 4 >= (1LL << 31) || (long long)g.N * g.H * g.W * g.C * 4 >= (1LL << 31)) return 0;
+    if (g.FH == 7 && g.FW == 7 && g.sh == 2 && g.pw == 3 && g.C == 3 && g.OC == 64) return 1;
+    return 0;
+}
+
+template <int FH, int FW, int S, int PW, int IC, int OCQ>
+int launch_sweep_deconv(const Geo &g, const float *dY, const float *Wt, float *dX, hipStream_t st)
+{
+    SweepDeconvParams P{};
+    P.dY = dY; P.W = Wt; P.dX = dX;
+    P.N = g.N; P.OH = g.OH; P.OW = g.OW; P.OC = g.OC; P.IH = g.H; P.IW = g.W; P.ph = g.ph;
+    const int need = (g.W + S - 1) / S;
+    P.OWv = need > g.OW ? need : g.OW;
+    using G = SweepShape<FH, FW, S, PW, IC, OCQ>;
+    const long long line = (long long)g.N * P.OWv;
+    const long long nWin = (line + G::ADV - 1) / G::ADV, rows = nWin * g.OH;
+    if (!fits_i31(rows) || !fits_i31(nWin * 64)) return CKS_ERR_SHAPE;
+    P.nWin = (int)nWin;
+    // one wave per SIMD, every wave an equal run of consecutive rows
+    const long long waves = rows < 4LL * kCUs ? rows : 4LL * kCUs;
+    P.per = (int)(rows / waves); P.rem = (int)(rows % waves);
+    P.dOWv = make_fastdiv(P.OWv); P.dOH = make_fastdiv(g.OH);
+    const int blocks = (int)((waves + 3) / 4);
+    return launch(kname("sweep_deconv", FH, FW, S, PW, IC, OCQ), sweep_deconv<FH, FW, S, PW, IC, OCQ>, P, blocks, 0, st);
+}
+
 size_t deconv_workspace(const Geo &g)
 {
     const size_t split = split_bytes(g.C, g.OC, g.FH, g.FW, g.sh, g.sw);
@@ -774,6 +808,8 @@ int deconv(const Geo &g, const float *dY, const float *Wt, float *dX, void *ws, 
     if (!fits_i31((long long)(split_bytes(C, OC, FH, FW, g.sh, g.sw) / sizeof(float)))) return CKS_ERR_SHAPE;
     if (!dY || !Wt || !dX) return CKS_ERR_NULL;
     // (the variant that reads the filter in place uses no workspace: it may then be NULL)
+    // (its 16-byte loads want dY aligned; it uses no workspace)
+    if (sweep_geometry(g) == 1 && aligned16(dY)) return launch_sweep_deconv<7, 7, 2, 3, 3, 4>(g, dY, Wt, dX, st);
     const bool have_ws = ws && ws_bytes >= deconv_workspace(g);
     ScatterPlan S = plan_scatter(g);
     if (S.ok && !have_ws) return CKS_ERR_WORKSPACE;

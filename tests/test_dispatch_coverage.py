@@ -72,7 +72,8 @@ def test_plan_of_the_benchmark_layers(cks):
     assert plan(cks.CKS_OP_DECONV2D, L1, 1) == ["pack_filter<0>", "rowrun_gemm<1, 64, 64, 2, 2, 0>"]   # dY off by a float: scalar loads
     assert plan(cks.CKS_OP_DILATED_CONV2D_WGRAD, L1) == ["pixel_gemm_dma<true>", "reduce_slices<16, 4>"]
     assert plan(cks.CKS_OP_CONV2D_FWD, L4b) == ["strip_fwd<7, 7, 3, 2>"]
-    assert plan(cks.CKS_OP_DECONV2D, L4b) == ["scatter_deconv<10, true>", "add_heads"]
+    assert plan(cks.CKS_OP_DECONV2D, L4b) == ["sweep_deconv<7, 7, 2, 3, 3, 4>"]                         # one launch, no workspace
+    assert plan(cks.CKS_OP_DECONV2D, L4b._replace(padding=2)) == ["scatter_deconv<10, true>", "add_heads"]   # another padding: the older stem kernel
     assert plan(cks.CKS_OP_DILATED_CONV2D_WGRAD, L4b) == ["strip_wgrad<7, 7, 3, 2, true>", "reduce_slices<16, 4>"]
     # bad geometry and a buffer that is too small are reported, not planned
     L = cks.lib()

@@ -146,6 +146,11 @@ MID = [
     ("stem_pad5_tiny", 3, 3, 7, 9, 12, 7, 7, 2, 5),
     ("stem_remainder_rows", 2, 3, 32, 31, 64, 7, 7, 2, 3),
     ("stem_single_pixel_rows", 1, 3, 9, 130, 64, 7, 7, 2, 3),
+    # sweep_deconv: waves with runs of two or three rows that start and end inside images and run on into the next
+    # window (2176 rows of 34 windows on 1024 waves); a line of columns that ends inside a window; one column per image
+    ("stem_runs_across_windows", 32, 3, 128, 128, 64, 7, 7, 2, 3),
+    ("stem_one_column_images", 70, 3, 16, 2, 64, 7, 7, 2, 3),
+    ("stem_tiny_image", 1, 3, 1, 1, 64, 7, 7, 2, 3),
     # the stem input gradient's check-free output steps start and end by padding and image height; with
     # padding 0 and width 38 the last band's row has three floats that no pixel reaches
     ("stem_oc64_pad0_unreached_columns", 2, 3, 75, 38, 64, 7, 7, 2, 0),
@@ -266,6 +271,10 @@ ASYM = [
     ("asym_patch_ic12_pixel_order", 9, 12, 11, 9, 40, 3, 3, (2, 1), (1, 1)),
     ("asym_rgb_7x7_pad", 3, 3, 30, 41, 64, 7, 7, (2, 2), (3, 2)),
     ("asym_rgb_3x3", 5, 3, 20, 70, 16, 3, 3, (1, 2), (1, 1)),
+    # the 7x7/s2 stem input gradient on the 4x4x1 matrix instruction takes any padding above and below (3 left and right)
+    ("asym_stem_sweep_ph1", 5, 3, 30, 41, 64, 7, 7, (2, 2), (1, 3)),
+    ("asym_stem_sweep_ph5_tall", 2, 3, 67, 26, 64, 7, 7, (2, 2), (5, 3)),
+    ("asym_stem_sweep_ph0_remainder", 3, 3, 38, 39, 64, 7, 7, (2, 2), (0, 3)),
     ("asym_gray", 4, 1, 12, 13, 70, 5, 3, (3, 2), (2, 0)),
     ("asym_remainder_rows", 16, 12, 8, 9, 32, 3, 3, (2, 3), (0, 0)),
     ("asym_one_by_one", 40, 48, 5, 6, 96, 1, 1, (2, 1), (0, 0)),
