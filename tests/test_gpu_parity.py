@@ -138,8 +138,9 @@ MID = [
     ("patch_ic3_pad_ge_filter", 6, 3, 6, 7, 8, 7, 7, 3, 7),
     ("gray_1ch", 5, 1, 10, 11, 70, 3, 3, 1, 1),
     ("ic7_5x5", 3, 7, 9, 9, 65, 5, 5, 1, 2),
-    # image stems: 7x7/s2 on 3 channels has kernels of its own (input strip in LDS; tap-stationary input
-    # gradient with 64 output channels), other few-channel layers take the generic variants of those
+    # image stems: 7x7/s2 on 3 channels has kernels of its own (input strip in LDS; input gradient with 64 output
+    # channels: on the 4x4x1 matrix instruction with padding 3, tap-stationary GEMM + LDS composing otherwise),
+    # other few-channel layers take the generic variants of those
     ("stem_oc64_ragged", 3, 3, 40, 37, 64, 7, 7, 2, 3),
     ("stem_oc70", 2, 3, 23, 50, 70, 7, 7, 2, 3),
     ("stem_pad0", 2, 3, 21, 33, 8, 7, 7, 2, 0),
