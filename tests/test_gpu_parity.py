@@ -324,6 +324,31 @@ def test_random_per_axis_geometries(cks, oracle, geo):
     check_layer(cks, oracle, synth.Layer(*geo), seed=900 + int(geo[0][5:]), kinds=("int",))
 
 
+def random_stem_geometries(count, seed):
+    """7x7 / stride 2 / 3 -> 64 channels with padding 3 left and right: the layers sweep_deconv serves, any height,
+    width, batch and vertical padding."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        N, H, W, ph = int(rng.integers(1, 9)), int(rng.integers(1, 90)), int(rng.integers(1, 150)), int(rng.integers(0, 7))
+        if H + 2 * ph < 7:
+            continue
+        out.append(("srand%02d" % len(out), N, 3, H, W, 64, 7, 7, (2, 2), (ph, 3)))
+    return out
+
+
+RANDOM_STEM = random_stem_geometries(16, 20230617)
+
+
+@pytest.mark.parametrize("geo", RANDOM_STEM, ids=[g[0] for g in RANDOM_STEM])
+def test_random_stem_geometries(cks, oracle, geo):
+    from paper_2306_15951_amd import synth
+
+    print("geometry", geo, flush=True)
+    assert [k for k, _ in cks.cks_plan_hw(cks.CKS_OP_DECONV2D, *geo[1:])] == ["sweep_deconv<7, 7, 2, 3, 3, 4>"]
+    check_layer(cks, oracle, synth.Layer(*geo), seed=1300 + int(geo[0][5:]), kinds=("int",))
+
+
 def structured_samples(shape, rng, n_random):
     """Random flat indices plus the corners / borders of every axis."""
     idx = [rng.integers(0, int(np.prod(shape)), size=n_random)]
@@ -825,7 +850,7 @@ def planned_calls():
 
     FWD, DECONV, WGRAD, SPLIT, PRESPLIT_OP, TRANSPOSE, PARTIALS, REDUCE, FWD_T, FWD_U, DECONV_U, WGRAD_U = range(12)
     calls = []
-    three = [tuple(synth.LAYERS["cfg0"])] + MID + RANDOM + ASYM + RANDOM_ASYM + WIDE_TILE
+    three = [tuple(synth.LAYERS["cfg0"])] + MID + RANDOM + ASYM + RANDOM_ASYM + RANDOM_STEM + WIDE_TILE
     three += [tuple(synth.LAYERS[n]) for n in FULL] + [("beyond_2GiB", 9, 64, 1024, 1024, 16, 3, 3, 1, 1)]
     for geo in three:
         calls += [(op, geo, 0) for op in (FWD, DECONV, WGRAD)]
