@@ -19,7 +19,8 @@ def cks():
 
 GRAPH_LAYERS = [
     ("graph_s2", 96, 64, 11, 9, 96, 3, 3, 2, 1),          # general kernels, filter read in place
-    ("graph_stem", 6, 3, 40, 37, 64, 7, 7, 2, 3),         # stem kernels: two launches for the input gradient
+    ("graph_stem", 6, 3, 40, 37, 64, 7, 7, 2, 3),         # stem kernels (input gradient: one launch on the 4x4x1 matrix instruction)
+    ("graph_stem_pad2", 6, 3, 40, 37, 64, 7, 7, 2, 2),    # stem kernels, another padding: two launches for the input gradient
 ]
 
 
