@@ -420,11 +420,11 @@ def test_tensors_beyond_2GiB_sampled(cks, oracle):
     check_layer(cks, oracle, L, seed=9, kinds=("normal",), samples=samples)
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg3b", "cfg4a"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg3a", "cfg3b", "cfg4a", "cfg4b"])
 def test_full_size_layers_every_element(cks, oracle, name):
-    """Three more benchmark layers compared in full (every output element of all three operators, integer
-    inputs, bit for bit): the stride-2 layer with its four sub-kernel classes, the 4x4-map layer whose
-    trimmed taps are 31 % of the filter, and the 4x4-filter upsampler."""
+    """The other benchmark layers compared in full (every output element of all three operators, integer
+    inputs, bit for bit): the stride-2 layer with its four sub-kernel classes, the two 512-channel layers (the
+    4x4 maps' trimmed taps are 31 % of the filter), the 4x4-filter upsampler and the 224x224 stem."""
     from paper_2306_15951_amd import synth
 
     L = synth.LAYERS[name]
